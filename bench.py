@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE verify layer on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM: moe_route_topk -> moe_permute -> moe_expert_up_swiglu -> moe_expert_down ->
+moe_combine -> spec_accept.  Prints ONE JSON line (see README / design notes for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..4] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_FP32_TFLOPS = 157.3       # fp32 vector
+PEAK_HBM_GBS = 8000.0          # HBM3E, published
+
+
+def cpu_baseline(cfg, L, draft, target, budget_s=15.0):
+    """The fp64 oracle, as it stands, timed on this machine's host cores on a bounded token sample."""
+    import numpy as np
+    from oracle import moe_verify_oracle as orc
+    from workloads import synth
+    try:
+        from threadpoolctl import threadpool_info
+        blas = [p.get("num_threads", 0) for p in threadpool_info() if p.get("user_api") == "blas"]
+        cores = max(blas) if blas else len(os.sched_getaffinity(0))
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    # input preparation (not timed): exact widening of the run-dtype tensors to fp64
+    wr = synth.to_f64(L["w_router"])
+    bias = None if L["bias"] is None else synth.to_f64(L["bias"])
+    wg = [synth.to_f64(L["w_gate"][e]) for e in range(cfg.E)]
+    wu = [synth.to_f64(L["w_up"][e]) for e in range(cfg.E)]
+    wd = [synth.to_f64(L["w_down"][e]) for e in range(cfg.E)]
+    x = synth.to_f64(L["x"])
+
+    def run(n):
+        t0 = time.perf_counter()
+        orc.moe_layer_stepwise(x[:n], wr, wg, wu, wd, cfg.k, bias, cfg.renorm)
+        orc.accept(draft.numpy(), target.numpy())
+        return time.perf_counter() - t0
+
+    n0 = min(cfg.T, 16)
+    t_probe = run(n0)
+    n = int(min(cfg.T, max(n0, n0 * budget_s / max(t_probe, 1e-6))))
+    t = run(n)
+    return {"value": n / t, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"fp64 numpy oracle (route, permute, grouped SwiGLU, combine, accept) on the "
+                      f"first {n} of {cfg.T} tokens of the same batch, all {cfg.E} experts' "
+                      f"weights widened to fp64 beforehand (untimed); {t:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4])
+    ap.add_argument("--seed", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2604_10152_amd as sm
+    from workloads import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    sm.load_library()
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    L = synth.make_layer(cfg, "cuda", seed=args.seed)
+    draft, target = synth.make_tokens(cfg, seed=args.seed)
+    draft_d, target_d = draft.cuda(), target.cuda()
+    alen = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
+    toks = torch.empty(cfg.B, cfg.gamma + 1, dtype=torch.int32, device="cuda")
+    layer = sm.MoEVerifyLayer(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
+                              renorm=cfg.renorm)
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
+                      stream=stream, up_events=ev)
+        sm.spec_accept(draft_d, target_d, alen, toks, stream)
+
+    for _ in range(args.warmup):
+        step()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    up_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
+
+    counts = (layer.expert_offsets[1:] - layer.expert_offsets[:-1]).cpu()
+    active = int((counts > 0).sum())
+    esize = 4 if cfg.dtype == "f32" else 2
+    P, d, f = cfg.P, cfg.d_model, cfg.d_ff
+    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+    tflops = cfg.flops() / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel: the gate/up expert GEMM with the SwiGLU epilogue (2/3 of the flops)
+    up_flops = 4.0 * P * d * f
+    up_bytes = (active * 2 * d * f + P * d + P * f) * esize
+    if cfg.dtype == "bf16" and args.config == 4:
+        roof = {"bound": "mfma", "achieved": up_flops / (up_ms * 1e-3) / 1e12,
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
+    elif cfg.dtype == "bf16":
+        roof = {"bound": "hbm", "achieved": up_bytes / (up_ms * 1e-3) / 1e9,
+                "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "alu", "achieved": up_flops / (up_ms * 1e-3) / 1e12,
+                "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["kernel"] = "grouped_gemm_bf16_kernel<up,swiglu>" if cfg.dtype == "bf16" else \
+        "grouped_gemm_f32_kernel<up,swiglu>"
+    roof["kernel_ms"] = up_ms
+    roof["traffic"] = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            roof["traffic"] = json.load(open(tpath)).get(f"cfg{args.config}")
+        except Exception:
+            roof["traffic"] = None
+
+    out = {
+        "metric": "moe_verify_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "gamma": cfg.gamma, "tokens": cfg.T,
+                   "d_model": d, "d_ff": f, "experts": cfg.E, "top_k": cfg.k,
+                   "active_experts": active, "max_rows_per_expert": int(counts.max())},
+        "tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else None,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, L, draft, target)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

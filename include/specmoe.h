@@ -1,0 +1,133 @@
+/*
+ * specmoe.h - C ABI of the MI355X (gfx950) MoE verification layer.
+ *
+ * The library computes, for one Mixture-of-Experts block, what the target model has to
+ * compute when it verifies a batch of speculative draft tokens (SpecMoE, arxiv 2604.10152):
+ * B sequences with gamma draft tokens each are scored in one parallel pass (Sec. 2.2
+ * "Algorithm", Fig. 4), so the block sees T = B*(gamma+1) tokens; its gate picks the top-K of
+ * E experts per token and only the picked experts run (Sec. 2.1, Fig. 1b); afterwards the
+ * greedy rule keeps the longest prefix of drafts that equals the target's own tokens and
+ * appends one target token (Sec. 2.2 Fig. 4 caption; Sec. 4 "SpecMoE configuration").
+ *
+ * Conventions shared by every entry point
+ *  - Every pointer except `stream` is a DEVICE pointer owned by the caller.  The library
+ *    never allocates, frees or keeps a pointer after the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work; they never synchronise.
+ *  - All matrices are dense row-major.  `dtype` selects the element type of activations and
+ *    weights (x, w_*, x_perm, y_perm, out, gain): SPECMOE_F32 = IEEE binary32,
+ *    SPECMOE_BF16 = bfloat16.  Gate weights are always float, indices always int32_t.
+ *  - Arguments are validated on the host before anything is enqueued.  A non-zero return
+ *    value (specmoe_status) means nothing was enqueued.  Sizes of zero tokens / sequences
+ *    are legal and enqueue nothing (moe_permute still writes expert_offsets).
+ *  - bf16 mode requires d_model % 64 == 0 and d_ff % 64 == 0; fp32 mode has no such limit.
+ *  - 1 <= k <= E <= SPECMOE_MAX_EXPERTS, k <= SPECMOE_MAX_TOPK.
+ *  - Results are deterministic: no floating-point atomics anywhere.
+ */
+#ifndef SPECMOE_H_
+#define SPECMOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPECMOE_OK = 0,
+    SPECMOE_ERR_NULL = 1,       /* a required pointer is NULL                       */
+    SPECMOE_ERR_SHAPE = 2,      /* negative size, k > E, unsupported divisibility   */
+    SPECMOE_ERR_DTYPE = 3,      /* dtype is neither SPECMOE_F32 nor SPECMOE_BF16     */
+    SPECMOE_ERR_WORKSPACE = 4,  /* workspace smaller than the query function says    */
+    SPECMOE_ERR_DEVICE = 5      /* the HIP runtime refused the launch                */
+} specmoe_status;
+
+typedef enum { SPECMOE_F32 = 0, SPECMOE_BF16 = 1 } specmoe_dtype;
+
+#define SPECMOE_MAX_EXPERTS 1024
+#define SPECMOE_MAX_TOPK 64
+
+/* Gate of one MoE block (Sec. 2.1: "the gate selects the top-K experts per token").
+ *   logits l[t,e] = router_bias[e] + sum_j x[t,j] * w_router[e,j], accumulated in fp64;
+ *   topk_idx[t,0..k-1] = the k experts with the largest LOGITS, slot order = descending
+ *   logit, equal logits -> lower expert id first;
+ *   topk_w[t,s] = softmax(l[t,:])[topk_idx[t,s]], divided by sum_s topk_w[t,s] if renorm != 0.
+ * x [T,d_model], w_router [E,d_model] in `dtype`; router_bias [E] float or NULL;
+ * topk_idx [T,k] int32; topk_w [T,k] float. */
+int moe_route_topk(const void* x, const void* w_router, const float* router_bias,
+                   int T, int d_model, int E, int k, int renorm, int dtype,
+                   int32_t* topk_idx, float* topk_w, void* stream);
+
+/* Grouping of the P = T*k (token, slot) pairs by expert (Fig. 2: tokens that activate the
+ * same expert are served together; Sec. 3.2: per-expert activation counts of the
+ * verification pass = expert_offsets[e+1] - expert_offsets[e]).
+ *   expert_offsets [E+1]: exclusive prefix sum of the per-expert pair counts;
+ *   row_src [P]: sorted row r holds flat pair row_src[r] = t*k + s;
+ *   row_of  [P]: inverse map, row_of[t*k+s] = r;
+ *   x_perm  [P,d_model]: x_perm[r] = x[row_src[r] / k]  (may be NULL: indices only).
+ * The sort is stable: inside an expert rows keep ascending flat pair index.  Every
+ * topk_idx value must lie in [0,E); values outside are clamped into the range. */
+int moe_permute(const void* x, const int32_t* topk_idx, int T, int d_model, int E, int k,
+                int dtype, void* x_perm, int32_t* expert_offsets, int32_t* row_src,
+                int32_t* row_of, void* stream);
+
+/* Bytes of scratch moe_grouped_swiglu needs for these sizes (0 on invalid arguments). */
+size_t moe_grouped_swiglu_workspace_bytes(int n_rows, int d_model, int d_ff, int E, int dtype);
+
+/* Experts (Sec. 2.1: each expert has the size of the FFN layer; only activated ones run).
+ * For every expert e and row r in [expert_offsets[e], expert_offsets[e+1]):
+ *   h = silu(x_perm[r] . w_gate[e]^T) * (x_perm[r] . w_up[e]^T),  silu(z) = z/(1+exp(-z))
+ *   y_perm[r] = h . w_down[e]^T
+ * x_perm, y_perm [n_rows,d_model]; w_gate, w_up [E,d_ff,d_model]; w_down [E,d_model,d_ff];
+ * expert_offsets [E+1] non-decreasing with expert_offsets[E] <= n_rows (device memory; it
+ * is never read on the host).  bf16 mode: bf16 operands, fp32 accumulation on the matrix
+ * cores, h and y_perm each rounded to bf16 once.  fp32 mode: fp32 FMA throughout.
+ * `workspace` holds h and must be 256-byte aligned. */
+int moe_grouped_swiglu(const void* x_perm, const int32_t* expert_offsets,
+                       const void* w_gate, const void* w_up, const void* w_down,
+                       int n_rows, int d_model, int d_ff, int E, int dtype,
+                       void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The two halves of moe_grouped_swiglu as separate calls (same definitions, same kernels):
+ *   moe_expert_up_swiglu:  h[r] = silu(x_perm[r] . w_gate[e]^T) * (x_perm[r] . w_up[e]^T)
+ *   moe_expert_down:       y_perm[r] = h[r] . w_down[e]^T
+ * h is [n_rows,d_ff] in `dtype`.  moe_grouped_swiglu(...) == up into `workspace`, then down. */
+int moe_expert_up_swiglu(const void* x_perm, const int32_t* expert_offsets, const void* w_gate,
+                         const void* w_up, int n_rows, int d_model, int d_ff, int E, int dtype,
+                         void* h, void* stream);
+int moe_expert_down(const void* h, const int32_t* expert_offsets, const void* w_down, int n_rows,
+                    int d_model, int d_ff, int E, int dtype, void* y_perm, void* stream);
+
+/* Gate-weighted mix of the selected experts' outputs (Sec. 2.1, Fig. 1b):
+ *   out[t] = (residual ? residual[t] : 0) + sum_{s<k} topk_w[t,s] * y_perm[row_of[t*k+s]]
+ * accumulated in fp32 in slot order, rounded once to `dtype`.  residual [T,d_model] in
+ * `dtype` or NULL; out may alias residual. */
+int moe_combine(const void* y_perm, const int32_t* row_of, const float* topk_w,
+                const void* residual, int T, int d_model, int k, int dtype, void* out,
+                void* stream);
+
+/* Greedy verification (Sec. 2.2 Fig. 4; Sec. 4: only drafts that exactly match the target's
+ * greedy tokens are accepted).  draft_ids [B,gamma]; target_ids [B,gamma+1], target_ids[b,i]
+ * being the target's token for the position draft_ids[b,i] was proposed for and
+ * target_ids[b,gamma] the extra token.  n_b = number of leading matches;
+ *   accept_len[b] = n_b + 1   (tokens generated this step, in [1,gamma+1]);
+ *   out_tokens[b,0..n_b] = target_ids[b,0..n_b], remaining entries -1.   gamma = 0 is legal. */
+int spec_accept(const int32_t* draft_ids, const int32_t* target_ids, int B, int gamma,
+                int32_t* accept_len, int32_t* out_tokens, void* stream);
+
+/* Helper for the multi-layer benchmark configuration (not part of the paper's method):
+ * out[t] = x[t] / sqrt(mean_j x[t,j]^2 + eps) * gain, fp32 arithmetic, rounded to `dtype`. */
+int moe_rmsnorm(const void* x, const void* gain, int T, int d_model, float eps, int dtype,
+                void* out, void* stream);
+
+/* Static description of a status code. */
+const char* specmoe_status_string(int status);
+
+/* ABI version of this header (bumped on any signature change). */
+int specmoe_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECMOE_H_ */

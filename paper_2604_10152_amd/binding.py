@@ -1,0 +1,186 @@
+"""ctypes binding of libspecmoe.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors that already live on the GPU (PyTorch owns device memory and
+streams); every computation happens in the library's HIP kernels.  There is no CPU or
+PyTorch fallback: if the library is missing, or a tensor is not a contiguous GPU tensor of
+the expected dtype, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTED_SYMBOLS = (
+    "moe_route_topk", "moe_permute", "moe_grouped_swiglu_workspace_bytes", "moe_grouped_swiglu",
+    "moe_expert_up_swiglu", "moe_expert_down", "moe_combine", "spec_accept", "moe_rmsnorm", "specmoe_status_string", "specmoe_abi_version",
+)
+
+F32, BF16 = 0, 1
+
+
+class SpecMoEError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libspecmoe.so")
+
+
+def load_library(build_if_missing: bool = True):
+    """dlopen the in-tree library; build it with hipcc first if it is not there."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        if not build_if_missing:
+            raise FileNotFoundError(path)
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(path)
+    vp, ip, fp = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    i, sz = ctypes.c_int, ctypes.c_size_t
+    lib.moe_route_topk.argtypes = [vp, vp, fp, i, i, i, i, i, i, ip, fp, vp]
+    lib.moe_permute.argtypes = [vp, ip, i, i, i, i, i, vp, ip, ip, ip, vp]
+    lib.moe_grouped_swiglu_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.moe_grouped_swiglu_workspace_bytes.restype = sz
+    lib.moe_grouped_swiglu.argtypes = [vp, ip, vp, vp, vp, i, i, i, i, i, vp, vp, sz, vp]
+    lib.moe_expert_up_swiglu.argtypes = [vp, ip, vp, vp, i, i, i, i, i, vp, vp]
+    lib.moe_expert_down.argtypes = [vp, ip, vp, i, i, i, i, i, vp, vp]
+    lib.moe_combine.argtypes = [vp, ip, fp, vp, i, i, i, i, vp, vp]
+    lib.spec_accept.argtypes = [ip, ip, i, i, ip, ip, vp]
+    lib.moe_rmsnorm.argtypes = [vp, vp, i, i, ctypes.c_float, i, vp, vp]
+    lib.specmoe_status_string.argtypes = [i]
+    lib.specmoe_status_string.restype = ctypes.c_char_p
+    lib.specmoe_abi_version.restype = i
+    for name in ("moe_route_topk", "moe_permute", "moe_grouped_swiglu", "moe_combine",
+                 "moe_expert_up_swiglu", "moe_expert_down",
+                 "spec_accept", "moe_rmsnorm"):
+        getattr(lib, name).restype = i
+    _LIB = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().specmoe_status_string(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: use float32 or bfloat16")
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    """Device pointer of a contiguous GPU tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor (no CPU fallback exists)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status, where):
+    if status != 0:
+        raise SpecMoEError(status, where)
+
+
+def moe_route_topk(x, w_router, router_bias, k, renorm, topk_idx, topk_w, stream=None):
+    T, d = x.shape
+    E = w_router.shape[0]
+    dt = _dtype_code(x)
+    _check(load_library().moe_route_topk(
+        _ptr(x, name="x"), _ptr(w_router, x.dtype, "w_router"),
+        _ptr(router_bias, torch.float32, "router_bias"), T, d, E, int(k), int(bool(renorm)), dt,
+        _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(topk_w, torch.float32, "topk_w"),
+        _stream(stream)), "moe_route_topk")
+
+
+def moe_permute(x, topk_idx, E, x_perm, expert_offsets, row_src, row_of, stream=None):
+    T, d = x.shape
+    k = topk_idx.shape[1]
+    _check(load_library().moe_permute(
+        _ptr(x, name="x"), _ptr(topk_idx, torch.int32, "topk_idx"), T, d, int(E), k,
+        _dtype_code(x), _ptr(x_perm, x.dtype, "x_perm"),
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), _ptr(row_src, torch.int32, "row_src"),
+        _ptr(row_of, torch.int32, "row_of"), _stream(stream)), "moe_permute")
+
+
+def moe_grouped_swiglu_workspace_bytes(n_rows, d_model, d_ff, E, dtype) -> int:
+    code = F32 if dtype == torch.float32 else BF16
+    return int(load_library().moe_grouped_swiglu_workspace_bytes(n_rows, d_model, d_ff, E, code))
+
+
+def moe_grouped_swiglu(x_perm, expert_offsets, w_gate, w_up, w_down, y_perm, workspace,
+                       stream=None):
+    n_rows, d = x_perm.shape
+    E, f, _ = w_gate.shape
+    _check(load_library().moe_grouped_swiglu(
+        _ptr(x_perm, name="x_perm"), _ptr(expert_offsets, torch.int32, "expert_offsets"),
+        _ptr(w_gate, x_perm.dtype, "w_gate"), _ptr(w_up, x_perm.dtype, "w_up"),
+        _ptr(w_down, x_perm.dtype, "w_down"), n_rows, d, f, E, _dtype_code(x_perm),
+        _ptr(y_perm, x_perm.dtype, "y_perm"), _ptr(workspace, torch.uint8, "workspace"),
+        workspace.numel(), _stream(stream)), "moe_grouped_swiglu")
+
+
+def moe_expert_up_swiglu(x_perm, expert_offsets, w_gate, w_up, h, stream=None):
+    n_rows, d = x_perm.shape
+    E, f, _ = w_gate.shape
+    _check(load_library().moe_expert_up_swiglu(
+        _ptr(x_perm, name="x_perm"), _ptr(expert_offsets, torch.int32, "expert_offsets"),
+        _ptr(w_gate, x_perm.dtype, "w_gate"), _ptr(w_up, x_perm.dtype, "w_up"), n_rows, d, f, E,
+        _dtype_code(x_perm), _ptr(h, x_perm.dtype, "h"), _stream(stream)), "moe_expert_up_swiglu")
+
+
+def moe_expert_down(h, expert_offsets, w_down, y_perm, stream=None):
+    n_rows, f = h.shape
+    E, d, _ = w_down.shape
+    _check(load_library().moe_expert_down(
+        _ptr(h, name="h"), _ptr(expert_offsets, torch.int32, "expert_offsets"),
+        _ptr(w_down, h.dtype, "w_down"), n_rows, d, f, E, _dtype_code(h),
+        _ptr(y_perm, h.dtype, "y_perm"), _stream(stream)), "moe_expert_down")
+
+
+def moe_combine(y_perm, row_of, topk_w, residual, out, stream=None):
+    T, k = topk_w.shape
+    d = y_perm.shape[1]
+    _check(load_library().moe_combine(
+        _ptr(y_perm, name="y_perm"), _ptr(row_of, torch.int32, "row_of"),
+        _ptr(topk_w, torch.float32, "topk_w"), _ptr(residual, y_perm.dtype, "residual"), T, d, k,
+        _dtype_code(y_perm), _ptr(out, y_perm.dtype, "out"), _stream(stream)), "moe_combine")
+
+
+def spec_accept(draft_ids, target_ids, accept_len, out_tokens, stream=None):
+    B, gamma = draft_ids.shape
+    if tuple(target_ids.shape) != (B, gamma + 1):
+        raise ValueError("target_ids must be [B, gamma+1]")
+    _check(load_library().spec_accept(
+        _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(target_ids, torch.int32, "target_ids"), B,
+        gamma, _ptr(accept_len, torch.int32, "accept_len"),
+        _ptr(out_tokens, torch.int32, "out_tokens"), _stream(stream)), "spec_accept")
+
+
+def moe_rmsnorm(x, gain, eps, out, stream=None):
+    T, d = x.shape
+    _check(load_library().moe_rmsnorm(
+        _ptr(x, name="x"), _ptr(gain, x.dtype, "gain"), T, d, float(eps), _dtype_code(x),
+        _ptr(out, x.dtype, "out"), _stream(stream)), "moe_rmsnorm")

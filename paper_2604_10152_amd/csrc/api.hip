@@ -1,0 +1,155 @@
+// C ABI of the library: argument validation on the host, then the kernel launchers.
+// Every entry point either enqueues all of its work on `stream` or (non-zero status) nothing.
+#include "../../include/specmoe.h"
+#include "common.h"
+
+#include <limits.h>
+
+using namespace specmoe;
+
+namespace {
+
+inline bool bad_dtype(int dt) { return dt != SPECMOE_F32 && dt != SPECMOE_BF16; }
+inline size_t esize(int dt) { return dt == SPECMOE_F32 ? 4 : 2; }
+inline int dev(hipError_t e) { return e == hipSuccess ? SPECMOE_OK : SPECMOE_ERR_DEVICE; }
+inline bool pairs_overflow(int T, int k) { return (long long)T * k > (long long)INT_MAX / 2; }
+
+}  // namespace
+
+extern "C" {
+
+int moe_route_topk(const void* x, const void* w_router, const float* router_bias, int T,
+                   int d_model, int E, int k, int renorm, int dtype, int32_t* topk_idx,
+                   float* topk_w, void* stream) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (T < 0 || d_model < 1 || E < 1 || E > SPECMOE_MAX_EXPERTS || k < 1 || k > E ||
+        k > SPECMOE_MAX_TOPK || pairs_overflow(T, k))
+        return SPECMOE_ERR_SHAPE;
+    if (T == 0) return SPECMOE_OK;
+    if (!x || !w_router || !topk_idx || !topk_w) return SPECMOE_ERR_NULL;
+    return dev(launch_route_topk(x, w_router, router_bias, T, d_model, E, k, renorm, dtype,
+                                 topk_idx, topk_w, (hipStream_t)stream));
+}
+
+int moe_permute(const void* x, const int32_t* topk_idx, int T, int d_model, int E, int k,
+                int dtype, void* x_perm, int32_t* expert_offsets, int32_t* row_src,
+                int32_t* row_of, void* stream) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (T < 0 || d_model < 1 || E < 1 || E > SPECMOE_MAX_EXPERTS || k < 1 || k > E ||
+        k > SPECMOE_MAX_TOPK || pairs_overflow(T, k))
+        return SPECMOE_ERR_SHAPE;
+    if (!expert_offsets) return SPECMOE_ERR_NULL;
+    if (T > 0 && (!topk_idx || !row_src || !row_of)) return SPECMOE_ERR_NULL;
+    if (T > 0 && x_perm && !x) return SPECMOE_ERR_NULL;
+    return dev(launch_permute(x, topk_idx, T, d_model, E, k, dtype, x_perm, expert_offsets,
+                              row_src, row_of, (hipStream_t)stream));
+}
+
+size_t moe_grouped_swiglu_workspace_bytes(int n_rows, int d_model, int d_ff, int E, int dtype) {
+    if (bad_dtype(dtype) || n_rows < 0 || d_model < 1 || d_ff < 1 || E < 1) return 0;
+    size_t h = (size_t)n_rows * (size_t)d_ff * esize(dtype);
+    return (h + 255) / 256 * 256 + 256;      // never 0 for valid arguments
+}
+
+static int check_expert_shapes(int n_rows, int d_model, int d_ff, int E, int dtype) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (n_rows < 0 || d_model < 1 || d_ff < 1 || E < 1 || E > SPECMOE_MAX_EXPERTS)
+        return SPECMOE_ERR_SHAPE;
+    if (dtype == SPECMOE_BF16 && (d_model % 64 != 0 || d_ff % 64 != 0)) return SPECMOE_ERR_SHAPE;
+    return SPECMOE_OK;
+}
+
+int moe_expert_up_swiglu(const void* x_perm, const int32_t* expert_offsets, const void* w_gate,
+                         const void* w_up, int n_rows, int d_model, int d_ff, int E, int dtype,
+                         void* h, void* stream) {
+    const int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
+    if (st != SPECMOE_OK) return st;
+    if (n_rows == 0) return SPECMOE_OK;
+    if (!x_perm || !expert_offsets || !w_gate || !w_up || !h) return SPECMOE_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (dtype == SPECMOE_F32)
+        return dev(launch_expert_up_f32((const float*)x_perm, expert_offsets, (const float*)w_gate,
+                                        (const float*)w_up, n_rows, d_model, d_ff, E, (float*)h, s));
+    return dev(launch_expert_up_bf16((const bf16_t*)x_perm, expert_offsets, (const bf16_t*)w_gate,
+                                     (const bf16_t*)w_up, n_rows, d_model, d_ff, E, (bf16_t*)h, s));
+}
+
+int moe_expert_down(const void* h, const int32_t* expert_offsets, const void* w_down, int n_rows,
+                    int d_model, int d_ff, int E, int dtype, void* y_perm, void* stream) {
+    const int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
+    if (st != SPECMOE_OK) return st;
+    if (n_rows == 0) return SPECMOE_OK;
+    if (!h || !expert_offsets || !w_down || !y_perm) return SPECMOE_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (dtype == SPECMOE_F32)
+        return dev(launch_expert_down_f32((const float*)h, expert_offsets, (const float*)w_down,
+                                          n_rows, d_model, d_ff, E, (float*)y_perm, s));
+    return dev(launch_expert_down_bf16((const bf16_t*)h, expert_offsets, (const bf16_t*)w_down,
+                                       n_rows, d_model, d_ff, E, (bf16_t*)y_perm, s));
+}
+
+int moe_grouped_swiglu(const void* x_perm, const int32_t* expert_offsets, const void* w_gate,
+                       const void* w_up, const void* w_down, int n_rows, int d_model, int d_ff,
+                       int E, int dtype, void* y_perm, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
+    if (st != SPECMOE_OK) return st;
+    if (n_rows == 0) return SPECMOE_OK;
+    if (!x_perm || !expert_offsets || !w_gate || !w_up || !w_down || !y_perm || !workspace)
+        return SPECMOE_ERR_NULL;
+    if (workspace_bytes < moe_grouped_swiglu_workspace_bytes(n_rows, d_model, d_ff, E, dtype) ||
+        ((uintptr_t)workspace & 255u) != 0)
+        return SPECMOE_ERR_WORKSPACE;
+    st = moe_expert_up_swiglu(x_perm, expert_offsets, w_gate, w_up, n_rows, d_model, d_ff, E,
+                              dtype, workspace, stream);
+    if (st != SPECMOE_OK) return st;
+    return moe_expert_down(workspace, expert_offsets, w_down, n_rows, d_model, d_ff, E, dtype,
+                           y_perm, stream);
+}
+
+int moe_combine(const void* y_perm, const int32_t* row_of, const float* topk_w,
+                const void* residual, int T, int d_model, int k, int dtype, void* out,
+                void* stream) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (T < 0 || d_model < 1 || k < 1 || k > SPECMOE_MAX_TOPK || pairs_overflow(T, k))
+        return SPECMOE_ERR_SHAPE;
+    if (T == 0) return SPECMOE_OK;
+    if (!y_perm || !row_of || !topk_w || !out) return SPECMOE_ERR_NULL;
+    return dev(launch_combine(y_perm, row_of, topk_w, residual, T, d_model, k, dtype, out,
+                              (hipStream_t)stream));
+}
+
+int spec_accept(const int32_t* draft_ids, const int32_t* target_ids, int B, int gamma,
+                int32_t* accept_len, int32_t* out_tokens, void* stream) {
+    if (B < 0 || gamma < 0 || (long long)B * (gamma + 1ll) > INT_MAX) return SPECMOE_ERR_SHAPE;
+    if (B == 0) return SPECMOE_OK;
+    if (!target_ids || !accept_len || !out_tokens || (gamma > 0 && !draft_ids))
+        return SPECMOE_ERR_NULL;
+    return dev(launch_spec_accept(draft_ids, target_ids, B, gamma, accept_len, out_tokens,
+                                  (hipStream_t)stream));
+}
+
+int moe_rmsnorm(const void* x, const void* gain, int T, int d_model, float eps, int dtype,
+                void* out, void* stream) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (T < 0 || d_model < 1 || !(eps >= 0.f)) return SPECMOE_ERR_SHAPE;
+    if (T == 0) return SPECMOE_OK;
+    if (!x || !gain || !out) return SPECMOE_ERR_NULL;
+    return dev(launch_rmsnorm(x, gain, T, d_model, eps, dtype, out, (hipStream_t)stream));
+}
+
+const char* specmoe_status_string(int status) {
+    switch (status) {
+        case SPECMOE_OK: return "ok";
+        case SPECMOE_ERR_NULL: return "a required pointer is NULL";
+        case SPECMOE_ERR_SHAPE: return "invalid or unsupported shape";
+        case SPECMOE_ERR_DTYPE: return "unknown dtype";
+        case SPECMOE_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case SPECMOE_ERR_DEVICE: return "HIP runtime error at launch";
+        default: return "unknown status";
+    }
+}
+
+int specmoe_abi_version(void) { return 1; }
+
+}  // extern "C"

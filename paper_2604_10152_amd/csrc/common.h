@@ -1,0 +1,67 @@
+// Shared device helpers and launcher declarations of the gfx950 MoE verify-layer library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace specmoe {
+
+constexpr int kWave = 64;           // CDNA wavefront width
+constexpr int kXcds = 8;            // MI355X: 8 accelerator dies, workgroups dealt round-robin
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+struct alignas(16) U128 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
+    return __uint_as_float(bits16 << 16);
+}
+__device__ __forceinline__ float load_as_float(const float* p) { return *p; }
+__device__ __forceinline__ float load_as_float(const bf16_t* p) { return (float)(*p); }
+__device__ __forceinline__ void store_from_float(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_from_float(bf16_t* p, float v) { *p = (bf16_t)v; }
+
+// Two floats -> packed bf16 pair (round to nearest even), low half = a.
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 v = {(bf16_t)a, (bf16_t)b};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + __expf(-z)); }
+
+// ---- launchers (host side, defined in the .hip files) -------------------------------
+hipError_t launch_route_topk(const void* x, const void* wr, const float* bias, int T, int d,
+                             int E, int k, int renorm, int dtype, int32_t* idx, float* w,
+                             hipStream_t s);
+hipError_t launch_permute(const void* x, const int32_t* idx, int T, int d, int E, int k,
+                          int dtype, void* x_perm, int32_t* offsets, int32_t* row_src,
+                          int32_t* row_of, hipStream_t s);
+hipError_t launch_expert_up_f32(const float* x_perm, const int32_t* offsets, const float* wg,
+                                const float* wu, int n_rows, int d, int f, int E, float* h,
+                                hipStream_t s);
+hipError_t launch_expert_down_f32(const float* h, const int32_t* offsets, const float* wd,
+                                  int n_rows, int d, int f, int E, float* y, hipStream_t s);
+hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, const bf16_t* wg,
+                                 const bf16_t* wu, int n_rows, int d, int f, int E, bf16_t* h,
+                                 hipStream_t s);
+hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, const bf16_t* wd,
+                                   int n_rows, int d, int f, int E, bf16_t* y, hipStream_t s);
+hipError_t launch_combine(const void* y_perm, const int32_t* row_of, const float* w,
+                          const void* residual, int T, int d, int k, int dtype, void* out,
+                          hipStream_t s);
+hipError_t launch_rmsnorm(const void* x, const void* gain, int T, int d, float eps, int dtype,
+                          void* out, hipStream_t s);
+hipError_t launch_spec_accept(const int32_t* draft, const int32_t* target, int B, int gamma,
+                              int32_t* accept_len, int32_t* out_tokens, hipStream_t s);
+
+}  // namespace specmoe

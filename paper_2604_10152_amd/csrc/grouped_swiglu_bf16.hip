@@ -1,0 +1,278 @@
+// Experts in bf16 mode: grouped SwiGLU FFN on the gfx950 matrix cores.
+// (SpecMoE Sec. 2.1: every expert is an FFN-sized block; only the rows routed to an expert
+// are multiplied with its weights.  At verification time all B*(gamma+1) tokens arrive at
+// once - Sec. 2.2 - which is what makes this a dense contraction worth the MFMA units.)
+//
+// Two launches: (1) h = silu(x Wg^T) * (x Wu^T) with gate and up columns of one f-range in
+// the same tile so the SwiGLU epilogue happens on the accumulators; (2) y = h Wd^T.
+// Both are "NT" GEMMs: A rows and W rows are contiguous along the contraction axis, which is
+// the layout v_mfma_f32_32x32x16_bf16 wants (each lane feeds 8 consecutive k of one row).
+//
+// Tiling: a workgroup owns BM rows of ONE expert x BN weight rows, BK = 64 per step, tiles
+// staged through LDS (double buffered, 16-byte chunks XOR-swizzled by row so that both the
+// 128-byte-row stores and the MFMA fragment reads are bank-conflict free).  m-tiles never
+// straddle experts; the tile -> (expert, n-tile, m-tile) map is computed on the device from
+// expert_offsets (no host read-back).  Workgroup ids are dealt round-robin to the 8 XCDs by
+// the hardware, so the map sends consecutive logical tiles - the m-tiles that share one
+// weight tile, then the next n-tile of the same expert - to the same XCD and its L2.
+// 32-row MFMA sub-tiles beyond the expert's last row are skipped (wave-uniform), and waves
+// take sub-tiles interleaved so that a partial tile stays balanced across the SIMDs.
+#include "common.h"
+
+namespace specmoe {
+namespace {
+
+constexpr int kBK = 64;                       // contraction elements per LDS stage
+constexpr int kChunksPerRow = kBK / 8;        // 16-byte chunks per tile row (8)
+
+template <int BM_, int BN_, int WM_, int WN_, bool SWIGLU_>
+struct TileCfg {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+    static constexpr bool SWIGLU = SWIGLU_;
+    static constexpr int THREADS = WM * WN * kWave;
+    static constexpr int TM = BM / (32 * WM);             // 32-row sub-tiles per wave
+    static constexpr int TN = BN / (32 * WN);             // 32-col sub-tiles per wave
+    static constexpr int A_LD = BM * kChunksPerRow / THREADS;   // 16-byte loads per thread
+    static constexpr int B_LD = BN * kChunksPerRow / THREADS;
+    static constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;   // output columns per tile
+    static constexpr size_t LDS_BYTES = 2ull * (BM + BN) * kBK * sizeof(bf16_t);
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "tile / wave grid mismatch");
+    static_assert((BM * kChunksPerRow) % THREADS == 0 && (BN * kChunksPerRow) % THREADS == 0,
+                  "loads must divide evenly");
+    static_assert(!SWIGLU || (TN % 2 == 0), "gate and up sub-tiles must pair up in one wave");
+};
+
+// element offset (bf16 units) of 16-byte chunk `c` of tile row `r` inside an LDS tile
+__device__ __forceinline__ int lds_off(int r, int c) { return r * kBK + ((c ^ (r & 7)) << 3); }
+
+template <typename C>
+__global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_kernel(
+    const bf16_t* __restrict__ A,        // [n_rows, K]
+    const int32_t* __restrict__ offsets, // [E+1]
+    const bf16_t* __restrict__ W0,       // [E, N, K]   (gate, or down)
+    const bf16_t* __restrict__ W1,       // [E, N, K]   (up; SWIGLU only)
+    int E, int N, int K, bf16_t* __restrict__ Cout /* [n_rows, N] */) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    bf16_t* lds_a = reinterpret_cast<bf16_t*>(lds_raw);                 // [2][BM*BK]
+    bf16_t* lds_b = lds_a + 2 * C::BM * kBK;                            // [2][BN*BK]
+
+    // ---- logical tile of this workgroup -------------------------------------------
+    const int NT = (N + C::BN_OUT - 1) / C::BN_OUT;
+    int total_mt = 0;
+    for (int e = 0; e < E; ++e) total_mt += (offsets[e + 1] - offsets[e] + C::BM - 1) / C::BM;
+    const long long G = (long long)total_mt * NT;
+    const long long per_xcd = (G + kXcds - 1) / kXcds;
+    const long long slot = blockIdx.x / kXcds;
+    const long long L = (long long)(blockIdx.x % kXcds) * per_xcd + slot;
+    if (slot >= per_xcd || L >= G) return;
+    int expert = 0, row0 = 0, tile_rows = 0, nt = 0;
+    {
+        long long base = 0;
+        for (int e = 0; e < E; ++e) {
+            const int lo = offsets[e], hi = offsets[e + 1];
+            const int mt = (hi - lo + C::BM - 1) / C::BM;
+            if (L < base + (long long)mt * NT) {
+                const long long rem = L - base;
+                nt = (int)(rem / mt);
+                const int mi = (int)(rem - (long long)nt * mt);
+                expert = e; row0 = lo + mi * C::BM; tile_rows = min(C::BM, hi - row0);
+                break;
+            }
+            base += (long long)mt * NT;
+        }
+    }
+    const int n0 = nt * C::BN_OUT;
+    const int nsub = (tile_rows + 31) / 32;              // active 32-row sub-tiles
+
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave-uniform by construction
+    const int wm = wave % C::WM, wn = wave / C::WM;
+
+    // ---- per-thread global load addresses (row clamped into the valid range) -------
+    const bf16_t* a_ptr[C::A_LD];
+    int a_lds[C::A_LD];
+#pragma unroll
+    for (int l = 0; l < C::A_LD; ++l) {
+        const int flat = tid + l * C::THREADS;
+        const int r = flat / kChunksPerRow, c = flat % kChunksPerRow;
+        a_ptr[l] = A + (size_t)(row0 + min(r, tile_rows - 1)) * K + c * 8;
+        a_lds[l] = lds_off(r, c);
+    }
+    const bf16_t* b_ptr[C::B_LD];
+    int b_lds[C::B_LD];
+    const bf16_t* w0 = W0 + (size_t)expert * N * K;
+    const bf16_t* w1 = C::SWIGLU ? W1 + (size_t)expert * N * K : nullptr;
+#pragma unroll
+    for (int l = 0; l < C::B_LD; ++l) {
+        const int flat = tid + l * C::THREADS;
+        const int r = flat / kChunksPerRow, c = flat % kChunksPerRow;
+        if (C::SWIGLU) {
+            const bool up = r >= C::BN / 2;
+            const int n = min(n0 + (up ? r - C::BN / 2 : r), N - 1);
+            b_ptr[l] = (up ? w1 : w0) + (size_t)n * K + c * 8;
+        } else {
+            b_ptr[l] = w0 + (size_t)min(n0 + r, N - 1) * K + c * 8;
+        }
+        b_lds[l] = lds_off(r, c);
+    }
+
+    // ---- fragment read offsets -------------------------------------------------------
+    // A sub-tile i of this wave covers tile rows 32*(wm + WM*i) .. +31 (interleaved);
+    // B sub-tile j covers weight rows nb(j) .. +31 of the LDS B tile.
+    int a_row[C::TM], b_row[C::TN];
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) a_row[i] = 32 * (wm + C::WM * i) + (lane & 31);
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) {
+        int nb;
+        if (C::SWIGLU) {
+            constexpr int H = C::TN / 2;
+            nb = (j < H) ? 32 * (wn * H + j) : C::BN / 2 + 32 * (wn * H + (j - H));
+        } else {
+            nb = 32 * (wn * C::TN + j);
+        }
+        b_row[j] = nb + (lane & 31);
+    }
+    const int khalf = lane >> 5;                        // which 8-wide k group of a 16-k step
+
+    floatx16 acc[C::TM][C::TN];
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    U128 a_reg[C::A_LD], b_reg[C::B_LD];
+    const int KT = K / kBK;
+
+    auto load_global = [&](int kt) {
+#pragma unroll
+        for (int l = 0; l < C::A_LD; ++l)
+            a_reg[l] = *reinterpret_cast<const U128*>(a_ptr[l] + (size_t)kt * kBK);
+#pragma unroll
+        for (int l = 0; l < C::B_LD; ++l)
+            b_reg[l] = *reinterpret_cast<const U128*>(b_ptr[l] + (size_t)kt * kBK);
+    };
+    auto store_lds = [&](int buf) {
+        bf16_t* sa = lds_a + buf * C::BM * kBK;
+        bf16_t* sb = lds_b + buf * C::BN * kBK;
+#pragma unroll
+        for (int l = 0; l < C::A_LD; ++l) *reinterpret_cast<U128*>(sa + a_lds[l]) = a_reg[l];
+#pragma unroll
+        for (int l = 0; l < C::B_LD; ++l) *reinterpret_cast<U128*>(sb + b_lds[l]) = b_reg[l];
+    };
+
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < KT) load_global(kt + 1);
+        const bf16_t* sa = lds_a + buf * C::BM * kBK;
+        const bf16_t* sb = lds_b + buf * C::BN * kBK;
+#pragma unroll
+        for (int kk = 0; kk < kBK / 16; ++kk) {
+            const int c = kk * 2 + khalf;
+            bf16x8 bf[C::TN];
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+                bf[j] = *reinterpret_cast<const bf16x8*>(sb + lds_off(b_row[j], c));
+#pragma unroll
+            for (int i = 0; i < C::TM; ++i) {
+                if (wm + C::WM * i < nsub) {             // wave-uniform: skip empty sub-tiles
+                    const bf16x8 af = *reinterpret_cast<const bf16x8*>(sa + lds_off(a_row[i], c));
+#pragma unroll
+                    for (int j = 0; j < C::TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf[j], acc[i][j],
+                                                                            0, 0, 0);
+                }
+            }
+        }
+        if (kt + 1 < KT) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: accumulator element r of a lane is row 8*(r/4) + 4*(lane/32) + r%4,
+    //      column lane%32 of its 32x32 sub-tile -------------------------------------------
+    const int col_in = lane & 31;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) {
+        if (wm + C::WM * i >= nsub) continue;
+        const int rbase = 32 * (wm + C::WM * i) + 4 * khalf;
+        if (C::SWIGLU) {
+            constexpr int H = C::TN / 2;
+#pragma unroll
+            for (int j = 0; j < H; ++j) {
+                const int col = n0 + 32 * (wn * H + j) + col_in;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = rbase + 8 * (r / 4) + (r % 4);
+                    if (row < tile_rows && col < N) {
+                        const float g = acc[i][j][r], u = acc[i][j + H][r];
+                        Cout[(size_t)(row0 + row) * N + col] = (bf16_t)(silu_f32(g) * u);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j) {
+                const int col = n0 + 32 * (wn * C::TN + j) + col_in;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = rbase + 8 * (r / 4) + (r % 4);
+                    if (row < tile_rows && col < N)
+                        Cout[(size_t)(row0 + row) * N + col] = (bf16_t)acc[i][j][r];
+                }
+            }
+        }
+    }
+}
+
+template <typename C>
+hipError_t launch_one(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
+                      const bf16_t* W1, int n_rows, int E, int N, int K, bf16_t* Cout,
+                      hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&grouped_gemm_bf16_kernel<C>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long long NT = (N + C::BN_OUT - 1) / C::BN_OUT;
+    const long long max_mt = n_rows / C::BM + E;     // sum_e ceil(M_e/BM) <= floor(P/BM) + E
+    long long grid = max_mt * NT;
+    grid = (grid + kXcds - 1) / kXcds * kXcds;
+    hipLaunchKernelGGL(grouped_gemm_bf16_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS),
+                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+static inline bool large_batch(int n_rows, int E) { return (long long)n_rows >= 128ll * E; }
+
+// Large batches (>= 128 rows per expert on average): 256-row tiles, 8 wavefronts, MFMA-bound.
+// Few rows per expert: the weights stream once from HBM and narrow tiles give every CU its
+// own stream.
+hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, const bf16_t* wg,
+                                 const bf16_t* wu, int n_rows, int d, int f, int E, bf16_t* h,
+                                 hipStream_t s) {
+    if (n_rows == 0) return hipSuccess;
+    if (large_batch(n_rows, E))
+        return launch_one<TileCfg<256, 256, 2, 4, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s);
+    return launch_one<TileCfg<64, 128, 1, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s);
+}
+
+hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, const bf16_t* wd,
+                                   int n_rows, int d, int f, int E, bf16_t* y, hipStream_t s) {
+    if (n_rows == 0) return hipSuccess;
+    if (large_batch(n_rows, E))
+        return launch_one<TileCfg<256, 256, 2, 4, false>>(h, offsets, wd, nullptr, n_rows, E, d, f, y, s);
+    return launch_one<TileCfg<64, 64, 1, 2, false>>(h, offsets, wd, nullptr, n_rows, E, d, f, y, s);
+}
+
+}  // namespace specmoe

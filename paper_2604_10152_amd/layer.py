@@ -1,0 +1,47 @@
+"""Buffers of one MoE verify layer plus the five library calls in order.  No arithmetic here:
+the class only owns the output / scratch tensors (allocated once) and marshals arguments."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class MoEVerifyLayer:
+    """route -> permute -> grouped SwiGLU -> combine on preallocated buffers.
+
+    T tokens = B sequences x (gamma+1) positions (the tokens one verification pass scores).
+    """
+
+    def __init__(self, T, d_model, d_ff, E, k, dtype, device="cuda", renorm=True):
+        self.T, self.d, self.f, self.E, self.k = T, d_model, d_ff, E, k
+        self.dtype, self.renorm = dtype, renorm
+        P = T * k
+        dev = torch.device(device)
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.topk_idx = torch.empty((T, k), **i32)
+        self.topk_w = torch.empty((T, k), dtype=torch.float32, device=dev)
+        self.expert_offsets = torch.empty((E + 1,), **i32)
+        self.row_src = torch.empty((P,), **i32)
+        self.row_of = torch.empty((P,), **i32)
+        self.x_perm = torch.empty((P, d_model), dtype=dtype, device=dev)
+        self.y_perm = torch.empty((P, d_model), dtype=dtype, device=dev)
+        self.out = torch.empty((T, d_model), dtype=dtype, device=dev)
+        self.h = torch.empty((P, d_ff), dtype=dtype, device=dev)
+
+    def forward(self, x, w_router, w_gate, w_up, w_down, bias=None, residual=None, out=None,
+                stream=None, up_events=None):
+        """Enqueues the layer.  `up_events`, if given, is a (start, end) pair of torch events
+        recorded around the gate/up expert GEMM (used by the benchmark's roofline figure)."""
+        out = self.out if out is None else out
+        B.moe_route_topk(x, w_router, bias, self.k, self.renorm, self.topk_idx, self.topk_w, stream)
+        B.moe_permute(x, self.topk_idx, self.E, self.x_perm, self.expert_offsets, self.row_src,
+                      self.row_of, stream)
+        if up_events is not None:
+            up_events[0].record(stream)
+        B.moe_expert_up_swiglu(self.x_perm, self.expert_offsets, w_gate, w_up, self.h, stream)
+        if up_events is not None:
+            up_events[1].record(stream)
+        B.moe_expert_down(self.h, self.expert_offsets, w_down, self.y_perm, stream)
+        B.moe_combine(self.y_perm, self.row_of, self.topk_w, residual, out, stream)
+        return out

@@ -1,0 +1,51 @@
+"""Helpers shared by the GPU parity tests (test-side only)."""
+import numpy as np
+import torch
+
+from workloads import synth
+from workloads.metrics import floored_rel_err, max_norm_err  # noqa: F401
+
+# Parity bars.  Integer outputs: bit-exact.  Floating outputs: the benchmark definition's
+# "max relative error" 1e-2 (bf16) / 1e-5 (fp32), measured per output row as
+# max_j |got - want| / max_j |want|  (see the design notes for why the denominator is the
+# row's largest magnitude and not each element's own).
+TOL = {torch.bfloat16: 1e-2, torch.float32: 1e-5}
+GATE_W_RTOL = 2e-6          # gate weights: fp64 on both sides, one rounding to fp32
+
+
+def row_rel_err(got, want):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    if want.size == 0:
+        return 0.0
+    den = np.abs(want).max(axis=1)
+    num = np.abs(got - want).max(axis=1)
+    floor = np.abs(want).max() * 1e-6 + 1e-300
+    return float((num / np.maximum(den, floor)).max())
+
+
+class LazyF64:
+    """Per-expert fp64 view of an [E, ...] tensor; widened only when an expert is used."""
+
+    def __init__(self, t):
+        self.t = t
+        self._cache = {}
+
+    def __len__(self):
+        return self.t.shape[0]
+
+    def __getitem__(self, e):
+        e = int(e)
+        if e not in self._cache:
+            if len(self._cache) >= 2:
+                self._cache.clear()
+            self._cache[e] = synth.to_f64(self.t[e])
+        return self._cache[e]
+
+
+def f64(t):
+    return synth.to_f64(t)
+
+
+def dev(t):
+    return None if t is None else t.to("cuda")

@@ -1,0 +1,369 @@
+"""Parity of the HIP library (through its C ABI) against the CPU oracle, element by element,
+on seeded inputs.  Needs an MI355X:  python -m pytest tests -m gpu"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_10152_amd as sm
+from oracle import moe_verify_oracle as orc
+from workloads import synth
+from _util import GATE_W_RTOL, TOL, LazyF64, dev, f64, row_rel_err
+
+pytestmark = pytest.mark.gpu
+I32 = torch.int32
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+# ------------------------------------------------------------------ a5 acceptance
+def _gpu_accept(draft, target):
+    B, gamma = draft.shape
+    alen = torch.full((B,), -7, dtype=I32, device="cuda")
+    out = torch.full((B, gamma + 1), -7, dtype=I32, device="cuda")
+    sm.spec_accept(dev(draft), dev(target), alen, out)
+    torch.cuda.synchronize()
+    return alen.cpu().numpy(), out.cpu().numpy()
+
+
+def test_accept_paper_example_and_exhaustive():
+    _say("spec_accept fig4 + exhaustive")
+    d = torch.tensor([[10, 11, 12, 13, 14]], dtype=I32)
+    t = torch.tensor([[10, 11, 12, 20, 21, 22]], dtype=I32)
+    alen, out = _gpu_accept(d, t)
+    assert alen.tolist() == [4] and out[0].tolist() == [10, 11, 12, 20, -1, -1]
+    for gamma in (1, 3, 7, 10):
+        pats = list(itertools.product((0, 1), repeat=gamma))
+        draft = torch.arange(len(pats) * gamma, dtype=I32).reshape(len(pats), gamma)
+        target = torch.cat([draft + 1 - torch.tensor(pats, dtype=I32),
+                            torch.full((len(pats), 1), 777, dtype=I32)], dim=1)
+        a, o = _gpu_accept(draft, target)
+        ea, eo = orc.accept(draft.numpy(), target.numpy())
+        assert (a == ea).all() and (o == eo).all()
+        assert a.min() >= 1 and a.max() <= gamma + 1
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 4, 5])
+def test_accept_configs(cfg_id):
+    cfg = synth.CONFIGS[cfg_id]
+    _say(f"spec_accept cfg{cfg_id}")
+    draft, target = synth.make_tokens(cfg, seed=cfg_id)
+    a, o = _gpu_accept(draft, target)
+    ea, eo = orc.accept(draft.numpy(), target.numpy())
+    assert (a == ea).all() and (o == eo).all()
+    fd, ft = synth.forced_accept_cases(cfg.gamma, cfg.vocab)
+    a, o = _gpu_accept(fd, ft)
+    assert a.tolist() == list(range(1, cfg.gamma + 2))
+    assert (o == orc.accept(fd.numpy(), ft.numpy())[1]).all()
+
+
+def test_accept_degenerate():
+    _say("spec_accept gamma=0, B=0")
+    d = torch.zeros((5, 0), dtype=I32)
+    t = torch.arange(5, dtype=I32).reshape(5, 1)
+    a, o = _gpu_accept(d, t)
+    assert a.tolist() == [1] * 5 and o[:, 0].tolist() == [0, 1, 2, 3, 4]
+    a, o = _gpu_accept(torch.zeros((0, 3), dtype=I32), torch.zeros((0, 4), dtype=I32))
+    assert a.shape == (0,)
+
+
+# ------------------------------------------------------------------ a1 router
+def _gpu_route(x, wr, bias, k, renorm):
+    T = x.shape[0]
+    idx = torch.full((T, k), -1, dtype=I32, device="cuda")
+    w = torch.full((T, k), -1.0, dtype=torch.float32, device="cuda")
+    sm.moe_route_topk(dev(x), dev(wr), dev(bias), k, renorm, idx, w)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), w.cpu().numpy()
+
+
+def _check_route(x, wr, bias, k, renorm):
+    idx, w = _gpu_route(x, wr, bias, k, renorm)
+    eidx, ew, _ = orc.route_topk(f64(x), f64(wr), k, None if bias is None else f64(bias), renorm)
+    assert (idx == eidx).all(), f"{(idx != eidx).sum()} routing indices differ"
+    assert np.allclose(w, ew, rtol=GATE_W_RTOL, atol=1e-30)
+    if renorm:
+        assert np.allclose(w.sum(axis=1), 1.0, atol=1e-6)
+
+
+@pytest.mark.parametrize("dtype,T,d,E,k,renorm,bias", [
+    (torch.float32, 16, 256, 8, 2, True, False),
+    (torch.float32, 37, 33, 5, 3, False, True),        # d not a multiple of the vector width
+    (torch.float32, 9, 8, 1, 1, True, False),
+    (torch.bfloat16, 320, 2048, 64, 6, True, True),
+    (torch.bfloat16, 130, 192, 130, 7, True, True),    # more experts than lanes
+    (torch.bfloat16, 50, 72, 16, 16, False, False),    # k = E
+    (torch.bfloat16, 2048, 4096, 8, 2, True, False),
+])
+def test_route_cases(dtype, T, d, E, k, renorm, bias):
+    _say(f"route {dtype} T={T} d={d} E={E} k={k}")
+    g = torch.Generator().manual_seed(T * 31 + E)
+    x = (torch.randn(T, d, generator=g) / d ** 0.5).to(dtype)
+    wr = torch.randn(E, d, generator=g).to(dtype)
+    b = torch.randn(E, generator=g) if bias else None
+    _check_route(x, wr, b, k, renorm)
+
+
+def test_route_ties_go_to_lower_expert_id():
+    _say("route ties")
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn(64, 512, generator=g).to(torch.bfloat16)
+    wr = torch.randn(12, 512, generator=g).to(torch.bfloat16)
+    wr[7] = wr[2]; wr[11] = wr[2]; wr[5] = wr[0]
+    idx, _ = _gpu_route(x, wr, None, 12, True)
+    eidx, _, logits = orc.route_topk(f64(x), f64(wr), 12)
+    assert (logits[:, 7] == logits[:, 2]).all()
+    assert (idx == eidx).all()
+    x0 = torch.zeros(4, 512, dtype=torch.bfloat16)       # all logits equal
+    idx0, w0 = _gpu_route(x0, wr, None, 3, True)
+    assert (idx0 == np.array([0, 1, 2])).all() and np.allclose(w0, 1 / 3, rtol=1e-6)
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4])
+def test_route_configs(cfg_id):
+    cfg = synth.CONFIGS[cfg_id]
+    _say(f"route cfg{cfg_id}")
+    g = torch.Generator().manual_seed(cfg_id)
+    x = (torch.randn(cfg.T, cfg.d_model, generator=g) * cfg.x_std).to(cfg.torch_dtype)
+    wr = (torch.randn(cfg.E, cfg.d_model, generator=g) * cfg.router_std).to(cfg.torch_dtype)
+    bias = None
+    if cfg.zipf > 0:
+        bias = -cfg.zipf * torch.log(torch.randperm(cfg.E, generator=g).float() + 1)
+    _check_route(x, wr, bias, cfg.k, cfg.renorm)
+
+
+# ------------------------------------------------------------------ a2 permutation
+def _gpu_permute(x, idx, E, want_rows=True):
+    T, k = idx.shape
+    P = T * k
+    off = torch.full((E + 1,), -3, dtype=I32, device="cuda")
+    rs = torch.full((P,), -3, dtype=I32, device="cuda")
+    ro = torch.full((P,), -3, dtype=I32, device="cuda")
+    xp = torch.zeros((P, x.shape[1]), dtype=x.dtype, device="cuda") if want_rows else None
+    sm.moe_permute(dev(x), dev(idx), E, xp, off, rs, ro)
+    torch.cuda.synchronize()
+    return off.cpu().numpy(), rs.cpu().numpy(), ro.cpu().numpy(), None if xp is None else xp.cpu()
+
+
+@pytest.mark.parametrize("dtype,T,d,E,k", [
+    (torch.float32, 16, 256, 8, 2),
+    (torch.float32, 37, 33, 11, 3),          # ragged everything, 4-byte chunks
+    (torch.bfloat16, 37, 17, 11, 3),         # 2-byte chunks
+    (torch.bfloat16, 320, 2048, 64, 6),
+    (torch.bfloat16, 2048, 4096, 8, 2),
+    (torch.bfloat16, 5000, 64, 256, 8),      # many pairs, many experts
+    (torch.bfloat16, 1, 64, 1024, 1),
+])
+def test_permute_cases(dtype, T, d, E, k):
+    _say(f"permute {dtype} T={T} d={d} E={E} k={k}")
+    rng = np.random.default_rng(T + E)
+    # skewed expert popularity with some experts never used
+    pop = rng.random(E) ** 3
+    pop[rng.random(E) < 0.2] = 0
+    pop[0] = max(pop[0], 1e-3)
+    if (pop > 0).sum() < k:
+        pop[:] = 1.0
+    idx = np.stack([rng.choice(E, size=k, replace=False, p=pop / pop.sum()) for _ in range(T)])
+    idx_t = torch.from_numpy(idx.astype(np.int32))
+    x = torch.randn(T, d, generator=torch.Generator().manual_seed(1)).to(dtype)
+    off, rs, ro, xp = _gpu_permute(x, idx_t, E)
+    counts, eoff, ers, ero = orc.permute(idx, E)
+    assert (off == eoff).all() and (rs == ers).all() and (ro == ero).all()
+    assert torch.equal(xp, x[torch.from_numpy(ers.astype(np.int64)) // k])
+    assert (np.bincount(rs // k, minlength=T) == k).all()
+
+
+def test_permute_degenerate():
+    _say("permute T=0 and indices-only")
+    x = torch.zeros((0, 64), dtype=torch.bfloat16)
+    off, rs, ro, _ = _gpu_permute(x, torch.zeros((0, 2), dtype=I32), 8)
+    assert (off == 0).all()
+    idx = torch.tensor([[1, 0], [1, 2]], dtype=I32)
+    off, rs, ro, xp = _gpu_permute(torch.ones(2, 64, dtype=torch.bfloat16), idx, 4, want_rows=False)
+    assert off.tolist() == [0, 1, 3, 4, 4] and rs.tolist() == [1, 0, 2, 3] and xp is None
+
+
+# ------------------------------------------------------------------ a3 experts
+def _gpu_grouped(xp, off, wg, wu, wd):
+    n, d = xp.shape
+    E, f, _ = wg.shape
+    y = torch.full((n, d), float("nan"), dtype=xp.dtype, device="cuda")
+    ws = torch.empty((sm.moe_grouped_swiglu_workspace_bytes(n, d, f, E, xp.dtype),),
+                     dtype=torch.uint8, device="cuda")
+    sm.moe_grouped_swiglu(dev(xp), dev(off), dev(wg), dev(wu), dev(wd), y, ws)
+    torch.cuda.synchronize()
+    return y.cpu()
+
+
+def _grouped_case(dtype, d, f, rows, seed):
+    E = len(rows)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    n = int(off[-1])
+    g = torch.Generator().manual_seed(seed)
+    xp = (torch.randn(n, d, generator=g) / d ** 0.5).to(dtype)
+    wg = (torch.randn(E, f, d, generator=g) * 0.5).to(dtype)
+    wu = (torch.randn(E, f, d, generator=g) * 0.5).to(dtype)
+    wd = (torch.randn(E, d, f, generator=g) * (0.5 / f ** 0.5)).to(dtype)
+    y = _gpu_grouped(xp, torch.from_numpy(off), wg, wu, wd)
+    ey = orc.grouped_swiglu(f64(xp), off, LazyF64(wg), LazyF64(wu), LazyF64(wd))
+    assert torch.isfinite(y.float()).all()
+    err = row_rel_err(f64(y), ey)
+    print(f"   rows={rows} err={err:.3e}", flush=True)
+    assert err <= TOL[dtype], err
+
+
+@pytest.mark.parametrize("d,f,rows", [
+    (256, 512, [5, 0, 7, 3, 2, 9, 1, 5]),            # cfg-1 shape
+    (100, 72, [3, 70, 0, 129]),                      # nothing divides the 64x64x16 tile
+    (64, 64, [1]),
+])
+def test_grouped_fp32(d, f, rows):
+    _say(f"grouped f32 d={d} f={f} rows={rows}")
+    _grouped_case(torch.float32, d, f, rows, seed=d + f)
+
+
+@pytest.mark.parametrize("d,f,rows", [
+    (256, 384, [300, 0, 37, 1, 513, 256]),           # large-batch tiles: full, ragged, empty
+    (512, 1408, [700, 650]),
+    (256, 384, [3, 0, 70, 1, 129, 64, 0, 0]),        # few rows per expert: narrow tiles
+    (2048, 1408, [0, 40, 1, 0, 310, 7, 0, 22]),      # cfg-3 shape, skewed
+    (64, 64, [1]),
+])
+def test_grouped_bf16(d, f, rows):
+    _say(f"grouped bf16 d={d} f={f} rows={rows}")
+    _grouped_case(torch.bfloat16, d, f, rows, seed=d + f)
+
+
+def test_expert_up_alone_matches_swiglu_definition():
+    """h = silu(x Wg^T) * (x Wu^T) checked on its own (the gate/up GEMM with its epilogue)."""
+    _say("expert up only")
+    rows = [200, 0, 61, 300]
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    g = torch.Generator().manual_seed(77)
+    d, f, E = 256, 384, 4
+    xp = (torch.randn(off[-1], d, generator=g) / 16).to(torch.bfloat16)
+    wg = torch.randn(E, f, d, generator=g).to(torch.bfloat16)
+    wu = torch.randn(E, f, d, generator=g).to(torch.bfloat16)
+    h = torch.full((int(off[-1]), f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    sm.moe_expert_up_swiglu(dev(xp), dev(torch.from_numpy(off)), dev(wg), dev(wu), h)
+    torch.cuda.synchronize()
+    x64 = f64(xp)
+    want = np.zeros((off[-1], f))
+    for e in range(E):
+        lo, hi = off[e], off[e + 1]
+        want[lo:hi] = orc.silu(x64[lo:hi] @ f64(wg[e]).T) * (x64[lo:hi] @ f64(wu[e]).T)
+    assert row_rel_err(f64(h), want) <= TOL[torch.bfloat16]
+
+
+# ------------------------------------------------------------------ a4 combine, helpers
+@pytest.mark.parametrize("dtype,T,d,k,res", [
+    (torch.float32, 16, 256, 2, False), (torch.float32, 7, 33, 3, True),
+    (torch.bfloat16, 320, 2048, 6, False), (torch.bfloat16, 33, 4096, 2, True),
+    (torch.bfloat16, 5, 24, 4, False),
+])
+def test_combine(dtype, T, d, k, res):
+    _say(f"combine {dtype} T={T} d={d} k={k} residual={res}")
+    g = torch.Generator().manual_seed(T + d)
+    y = torch.randn(T * k, d, generator=g).to(dtype)
+    w = torch.rand(T, k, generator=g)
+    w = (w / w.sum(dim=1, keepdim=True)).float()
+    ro = torch.randperm(T * k, generator=g).to(I32)
+    r = torch.randn(T, d, generator=g).to(dtype) if res else None
+    out = torch.empty(T, d, dtype=dtype, device="cuda")
+    sm.moe_combine(dev(y), dev(ro), dev(w), dev(r), out)
+    torch.cuda.synchronize()
+    want = orc.combine(f64(y), ro.numpy(), f64(w), T, k) + (f64(r) if res else 0.0)
+    assert row_rel_err(f64(out), want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,T,d", [(torch.float32, 5, 100), (torch.bfloat16, 160, 4096)])
+def test_rmsnorm(dtype, T, d):
+    _say(f"rmsnorm {dtype} T={T} d={d}")
+    g = torch.Generator().manual_seed(d)
+    x = torch.randn(T, d, generator=g).to(dtype)
+    gain = (1 + 0.1 * torch.randn(d, generator=g)).to(dtype)
+    out = torch.empty(T, d, dtype=dtype, device="cuda")
+    sm.moe_rmsnorm(dev(x), dev(gain), 1e-5, out)
+    torch.cuda.synchronize()
+    assert row_rel_err(f64(out), orc.rmsnorm(f64(x), f64(gain), 1e-5)) <= TOL[dtype]
+
+
+# ------------------------------------------------------------------ whole layer
+def _run_layer(cfg, L):
+    layer = sm.MoEVerifyLayer(L["x"].shape[0], cfg.d_model, cfg.d_ff, cfg.E, cfg.k,
+                              cfg.torch_dtype, renorm=cfg.renorm)
+    out = layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"])
+    torch.cuda.synchronize()
+    return layer, out
+
+
+def _check_routing_and_permutation(cfg, L, layer):
+    x64 = f64(L["x"])
+    bias = None if L["bias"] is None else f64(L["bias"])
+    eidx, ew, _ = orc.route_topk(x64, f64(L["w_router"]), cfg.k, bias, cfg.renorm)
+    assert (layer.topk_idx.cpu().numpy() == eidx).all()
+    assert np.allclose(layer.topk_w.cpu().numpy(), ew, rtol=GATE_W_RTOL, atol=1e-30)
+    counts, eoff, ers, ero = orc.permute(eidx, cfg.E)
+    assert (layer.expert_offsets.cpu().numpy() == eoff).all()
+    assert (layer.row_src.cpu().numpy() == ers).all()
+    assert (layer.row_of.cpu().numpy() == ero).all()
+    return counts
+
+
+@pytest.mark.parametrize("cfg_id", [1, 3])
+def test_layer_full_oracle(cfg_id):
+    """Configurations the oracle can evaluate in full in seconds."""
+    cfg = synth.CONFIGS[cfg_id]
+    _say(f"layer cfg{cfg_id} full")
+    L = synth.make_layer(cfg, "cuda", seed=cfg_id)
+    layer, out = _run_layer(cfg, L)
+    counts = _check_routing_and_permutation(cfg, L, layer)
+    want = orc.moe_layer_stepwise(f64(L["x"]), f64(L["w_router"]), LazyF64(L["w_gate"]),
+                                  LazyF64(L["w_up"]), LazyF64(L["w_down"]), cfg.k,
+                                  None if L["bias"] is None else f64(L["bias"]), cfg.renorm)
+    err = row_rel_err(f64(out), want)
+    print(f"   cfg{cfg_id}: err={err:.3e} active={int((counts > 0).sum())}/{cfg.E} "
+          f"skew={orc.skewness(counts):.2f} hottest={int(counts.max())}", flush=True)
+    assert err <= TOL[cfg.torch_dtype]
+    # run twice: deterministic, bit-identical
+    out2 = layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"]).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("cfg_id,n_sample", [(2, 24), (4, 24)])
+def test_layer_sampled_tokens(cfg_id, n_sample):
+    """Full-size Mixtral-shaped layers in the launch configuration the benchmark times:
+    routing and permutation checked in full; outputs on a seeded token sample (tokens are
+    independent, so the per-token definition applies row by row)."""
+    cfg = synth.CONFIGS[cfg_id]
+    _say(f"layer cfg{cfg_id} sampled")
+    L = synth.make_layer(cfg, "cuda", seed=cfg_id)
+    layer, out = _run_layer(cfg, L)
+    _check_routing_and_permutation(cfg, L, layer)
+    rng = np.random.default_rng(cfg_id)
+    sample = np.sort(rng.choice(cfg.T, size=n_sample, replace=False))
+    xs = f64(L["x"][torch.from_numpy(sample).cuda()])
+    want = orc.moe_layer_brute_force(xs, f64(L["w_router"]), LazyF64(L["w_gate"]),
+                                     LazyF64(L["w_up"]), LazyF64(L["w_down"]), cfg.k, None, cfg.renorm)
+    got = f64(out[torch.from_numpy(sample).cuda()])
+    err = row_rel_err(got, want)
+    print(f"   cfg{cfg_id}: sampled-row err={err:.3e}", flush=True)
+    assert err <= TOL[cfg.torch_dtype]
+    assert torch.isfinite(out.float()).all()
+
+
+def test_identical_experts_invariant_on_gpu():
+    """All experts share weights + renormalised gates => out = FFN(x) whatever the routing."""
+    _say("layer identical experts")
+    cfg = synth.MoEConfig("ident", "bf16", 256, 384, 6, 3, 50, 3, 1 / 16, 0.05, 1.0)
+    L = synth.make_layer(cfg, "cuda", seed=9)
+    for n in ("w_gate", "w_up", "w_down"):
+        L[n] = L[n][:1].expand(cfg.E, -1, -1).contiguous()
+    layer, out = _run_layer(cfg, L)
+    want = orc.expert_ffn(f64(L["x"]), f64(L["w_gate"][0]), f64(L["w_up"][0]), f64(L["w_down"][0]))
+    assert row_rel_err(f64(out), want) <= TOL[torch.bfloat16]

@@ -1,0 +1,114 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, and rejects invalid arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2604_10152_amd as sm
+from paper_2604_10152_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "specmoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
+    return sorted({n for n in names if n.startswith(("moe_", "spec_", "specmoe_"))})
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return sm.load_library()
+
+
+def test_header_and_library_agree(lib):
+    declared = _declared_functions()
+    assert set(declared) == set(binding.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.specmoe_abi_version() == 1
+
+
+def test_status_strings(lib):
+    seen = {sm.status_string(s) for s in range(6)}
+    assert len(seen) == 6 and "ok" in seen
+    assert sm.status_string(99) == "unknown status"
+
+
+def test_workspace_query(lib):
+    q = lib.moe_grouped_swiglu_workspace_bytes
+    assert q(0, 8, 8, 1, 0) > 0
+    assert q(32, 256, 512, 8, 0) >= 32 * 512 * 4
+    assert q(4096, 4096, 14336, 8, 1) >= 4096 * 14336 * 2
+    assert q(4096, 4096, 14336, 8, 1) % 256 == 0
+    assert q(-1, 8, 8, 1, 0) == 0 and q(1, 8, 8, 1, 7) == 0 and q(1, 0, 8, 1, 0) == 0
+
+
+P = ctypes.c_void_p(0x1000)   # never dereferenced: validation fails first in every call below
+N = None
+
+
+def test_route_validation(lib):
+    f = lib.moe_route_topk
+    assert f(P, P, N, 4, 8, 8, 2, 1, 5, P, P, N) == 3            # dtype
+    assert f(P, P, N, 4, 8, 8, 9, 1, 0, P, P, N) == 2            # k > E
+    assert f(P, P, N, 4, 8, 0, 1, 1, 0, P, P, N) == 2            # E < 1
+    assert f(P, P, N, 4, 8, 2000, 1, 1, 0, P, P, N) == 2         # E too large
+    assert f(P, P, N, -1, 8, 8, 2, 1, 0, P, P, N) == 2           # T < 0
+    assert f(P, P, N, 4, 0, 8, 2, 1, 0, P, P, N) == 2            # d < 1
+    assert f(P, P, N, 2 ** 30, 8, 8, 8, 1, 0, P, P, N) == 2      # T*k overflows
+    assert f(N, P, N, 4, 8, 8, 2, 1, 0, P, P, N) == 1            # null x
+    assert f(P, P, N, 4, 8, 8, 2, 1, 0, N, P, N) == 1            # null idx
+    assert f(N, N, N, 0, 8, 8, 2, 1, 0, N, N, N) == 0            # T = 0 is legal
+
+
+def test_permute_validation(lib):
+    f = lib.moe_permute
+    assert f(P, P, 4, 8, 8, 2, 9, P, P, P, P, N) == 3
+    assert f(P, P, 4, 8, 8, 9, 0, P, P, P, P, N) == 2
+    assert f(P, P, 4, 8, 8, 2, 0, P, N, P, P, N) == 1            # offsets required
+    assert f(P, N, 4, 8, 8, 2, 0, P, P, P, P, N) == 1
+    assert f(N, P, 4, 8, 8, 2, 0, P, P, P, P, N) == 1            # x_perm wanted but x missing
+
+
+def test_grouped_validation(lib):
+    f = lib.moe_grouped_swiglu
+    big = 1 << 40
+    assert f(P, P, P, P, P, 8, 64, 64, 2, 4, P, P, big, N) == 3
+    assert f(P, P, P, P, P, -8, 64, 64, 2, 0, P, P, big, N) == 2
+    assert f(P, P, P, P, P, 8, 60, 64, 2, 1, P, P, big, N) == 2   # bf16 needs d % 64 == 0
+    assert f(P, P, P, P, P, 8, 64, 100, 2, 1, P, P, big, N) == 2  # bf16 needs f % 64 == 0
+    assert f(N, P, P, P, P, 8, 64, 64, 2, 1, P, P, big, N) == 1
+    assert f(P, P, P, P, P, 8, 64, 64, 2, 1, P, N, big, N) == 1
+    assert f(P, P, P, P, P, 8, 64, 64, 2, 1, P, P, 16, N) == 4    # workspace too small
+    assert f(P, P, P, P, P, 8, 64, 64, 2, 1, P, ctypes.c_void_p(0x1010), big, N) == 4  # misaligned
+    assert f(N, N, N, N, N, 0, 64, 64, 2, 1, N, N, 0, N) == 0     # no rows: nothing to do
+
+
+def test_combine_accept_rmsnorm_validation(lib):
+    c = lib.moe_combine
+    assert c(P, P, P, N, 4, 8, 2, 3, P, N) == 3
+    assert c(P, P, P, N, 4, 8, 0, 0, P, N) == 2
+    assert c(P, P, P, N, 4, 8, 2, 0, N, N) == 1
+    assert c(N, N, N, N, 0, 8, 2, 0, N, N) == 0
+    a = lib.spec_accept
+    assert a(P, P, -1, 3, P, P, N) == 2
+    assert a(P, P, 4, -3, P, P, N) == 2
+    assert a(N, P, 4, 3, P, P, N) == 1
+    assert a(P, P, 4, 3, N, P, N) == 1
+    assert a(N, N, 0, 3, N, N, N) == 0
+    r = lib.moe_rmsnorm
+    assert r(P, P, 4, 8, 1e-5, 2, P, N) == 3
+    assert r(P, P, 4, 8, -1.0, 0, P, N) == 2
+    assert r(P, N, 4, 8, 1e-5, 0, P, N) == 1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(4, 8)
+    with pytest.raises(TypeError):
+        sm.moe_route_topk(x, torch.zeros(2, 8), None, 1, True, torch.zeros(4, 1, dtype=torch.int32),
+                          torch.zeros(4, 1), stream=object())
