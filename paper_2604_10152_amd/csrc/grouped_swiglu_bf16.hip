@@ -19,6 +19,8 @@
 // take sub-tiles interleaved so that a partial tile stays balanced across the SIMDs.
 #include "common.h"
 
+#include <type_traits>
+
 namespace specmoe {
 namespace {
 
@@ -88,32 +90,31 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave-uniform by construction
     const int wm = wave % C::WM, wn = wave / C::WM;
 
-    // ---- per-thread global load addresses (row clamped into the valid range) -------
-    const bf16_t* a_ptr[C::A_LD];
-    int a_lds[C::A_LD];
+    // ---- per-thread global load offsets (elements, relative to uniform base pointers; rows
+    //      clamped into the valid range so every load stays in bounds) ---------------------
+    constexpr int kRowsPerPass = C::THREADS / kChunksPerRow;    // tile rows one load pass covers
+    static_assert(!C::SWIGLU || (C::BN / 2) % kRowsPerPass == 0, "gate/up split must align");
+    const bf16_t* a_base = A + (size_t)row0 * K;
+    const bf16_t* w0 = W0 + ((size_t)expert * N + min(n0, N - 1)) * K;
+    const bf16_t* w1 = C::SWIGLU ? W1 + ((size_t)expert * N + min(n0, N - 1)) * K : nullptr;
+    const int n_left = N - n0;                             // weight rows left from n0 (>= 1)
+    uint32_t a_off[C::A_LD], b_off[C::B_LD];
+    int a_lds[C::A_LD], b_lds[C::B_LD];
+    {
+        const int r0 = tid / kChunksPerRow, c = tid % kChunksPerRow;
 #pragma unroll
-    for (int l = 0; l < C::A_LD; ++l) {
-        const int flat = tid + l * C::THREADS;
-        const int r = flat / kChunksPerRow, c = flat % kChunksPerRow;
-        a_ptr[l] = A + (size_t)(row0 + min(r, tile_rows - 1)) * K + c * 8;
-        a_lds[l] = lds_off(r, c);
-    }
-    const bf16_t* b_ptr[C::B_LD];
-    int b_lds[C::B_LD];
-    const bf16_t* w0 = W0 + (size_t)expert * N * K;
-    const bf16_t* w1 = C::SWIGLU ? W1 + (size_t)expert * N * K : nullptr;
-#pragma unroll
-    for (int l = 0; l < C::B_LD; ++l) {
-        const int flat = tid + l * C::THREADS;
-        const int r = flat / kChunksPerRow, c = flat % kChunksPerRow;
-        if (C::SWIGLU) {
-            const bool up = r >= C::BN / 2;
-            const int n = min(n0 + (up ? r - C::BN / 2 : r), N - 1);
-            b_ptr[l] = (up ? w1 : w0) + (size_t)n * K + c * 8;
-        } else {
-            b_ptr[l] = w0 + (size_t)min(n0 + r, N - 1) * K + c * 8;
+        for (int l = 0; l < C::A_LD; ++l) {
+            const int r = r0 + l * kRowsPerPass;
+            a_off[l] = (uint32_t)(min(r, tile_rows - 1) * K + c * 8);
+            a_lds[l] = lds_off(r, c);
         }
-        b_lds[l] = lds_off(r, c);
+#pragma unroll
+        for (int l = 0; l < C::B_LD; ++l) {
+            const int r = r0 + l * kRowsPerPass;
+            const int rn = (C::SWIGLU && r >= C::BN / 2) ? r - C::BN / 2 : r;
+            b_off[l] = (uint32_t)(min(rn, n_left - 1) * K + c * 8);
+            b_lds[l] = lds_off(r, c);
+        }
     }
 
     // ---- fragment read offsets -------------------------------------------------------
@@ -135,26 +136,23 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_kernel(
     }
     const int khalf = lane >> 5;                        // which 8-wide k group of a 16-k step
 
-    floatx16 acc[C::TM][C::TN];
-#pragma unroll
-    for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < C::TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
     U128 a_reg[C::A_LD], b_reg[C::B_LD];
     const int KT = K / kBK;
 
-    auto load_global = [&](int kt) {
+    auto load_global = [&](int kt) __attribute__((always_inline)) {
+        const bf16_t* ak = a_base + (size_t)kt * kBK;
+        const bf16_t* w0k = w0 + (size_t)kt * kBK;
+        const bf16_t* w1k = C::SWIGLU ? w1 + (size_t)kt * kBK : nullptr;
 #pragma unroll
         for (int l = 0; l < C::A_LD; ++l)
-            a_reg[l] = *reinterpret_cast<const U128*>(a_ptr[l] + (size_t)kt * kBK);
+            a_reg[l] = *reinterpret_cast<const U128*>(ak + a_off[l]);
 #pragma unroll
-        for (int l = 0; l < C::B_LD; ++l)
-            b_reg[l] = *reinterpret_cast<const U128*>(b_ptr[l] + (size_t)kt * kBK);
+        for (int l = 0; l < C::B_LD; ++l) {
+            const bool up = C::SWIGLU && (l * kRowsPerPass >= C::BN / 2);   // compile-time per l
+            b_reg[l] = *reinterpret_cast<const U128*>((up ? w1k : w0k) + b_off[l]);
+        }
     };
-    auto store_lds = [&](int buf) {
+    auto store_lds = [&](int buf) __attribute__((always_inline)) {
         bf16_t* sa = lds_a + buf * C::BM * kBK;
         bf16_t* sb = lds_b + buf * C::BN * kBK;
 #pragma unroll
@@ -163,70 +161,97 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_kernel(
         for (int l = 0; l < C::B_LD; ++l) *reinterpret_cast<U128*>(sb + b_lds[l]) = b_reg[l];
     };
 
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
+    // Number of this wave's sub-tiles that hold real rows.  Sub-tile i sits at tile row
+    // 32*(wm + WM*i), so the active ones are exactly i = 0 .. ta-1.  The main loop and the
+    // epilogue are instantiated once per value of ta: straight-line MFMA code in each, and a
+    // partial tile issues only the matrix instructions it needs.
+    const int ta = min(C::TM, max(0, (nsub - wm + C::WM - 1) / C::WM));
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) load_global(kt + 1);
-        const bf16_t* sa = lds_a + buf * C::BM * kBK;
-        const bf16_t* sb = lds_b + buf * C::BN * kBK;
+    auto run = [&](auto ta_tag) __attribute__((always_inline)) {
+        constexpr int TA = decltype(ta_tag)::value;
+        floatx16 acc[TA > 0 ? TA : 1][C::TN];
 #pragma unroll
-        for (int kk = 0; kk < kBK / 16; ++kk) {
-            const int c = kk * 2 + khalf;
-            bf16x8 bf[C::TN];
+        for (int i = 0; i < TA; ++i)
 #pragma unroll
             for (int j = 0; j < C::TN; ++j)
-                bf[j] = *reinterpret_cast<const bf16x8*>(sb + lds_off(b_row[j], c));
 #pragma unroll
-            for (int i = 0; i < C::TM; ++i) {
-                if (wm + C::WM * i < nsub) {             // wave-uniform: skip empty sub-tiles
-                    const bf16x8 af = *reinterpret_cast<const bf16x8*>(sa + lds_off(a_row[i], c));
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        load_global(0);
+        store_lds(0);
+        __syncthreads();
+
+        for (int kt = 0; kt < KT; ++kt) {
+            const int buf = kt & 1;
+            // branch-free prefetch: the last step re-loads its own tile into the idle buffer
+            load_global(min(kt + 1, KT - 1));
+            const bf16_t* sa = lds_a + buf * C::BM * kBK;
+            const bf16_t* sb = lds_b + buf * C::BN * kBK;
+            if (TA > 0) {
+#pragma unroll
+                for (int kk = 0; kk < kBK / 16; ++kk) {
+                    const int c = kk * 2 + khalf;
+                    bf16x8 bf[C::TN], af[TA > 0 ? TA : 1];
 #pragma unroll
                     for (int j = 0; j < C::TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf[j], acc[i][j],
-                                                                            0, 0, 0);
+                        bf[j] = *reinterpret_cast<const bf16x8*>(sb + lds_off(b_row[j], c));
+#pragma unroll
+                    for (int i = 0; i < TA; ++i)
+                        af[i] = *reinterpret_cast<const bf16x8*>(sa + lds_off(a_row[i], c));
+#pragma unroll
+                    for (int i = 0; i < TA; ++i)
+#pragma unroll
+                        for (int j = 0; j < C::TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                af[i], bf[j], acc[i][j], 0, 0, 0);
                 }
             }
+            store_lds(buf ^ 1);
+            __syncthreads();
         }
-        if (kt + 1 < KT) store_lds(buf ^ 1);
-        __syncthreads();
-    }
 
-    // ---- epilogue: accumulator element r of a lane is row 8*(r/4) + 4*(lane/32) + r%4,
-    //      column lane%32 of its 32x32 sub-tile -------------------------------------------
-    const int col_in = lane & 31;
+        // epilogue: accumulator element r of a lane is row 8*(r/4) + 4*(lane/32) + r%4,
+        // column lane%32 of its 32x32 sub-tile
+        const int col_in = lane & 31;
 #pragma unroll
-    for (int i = 0; i < C::TM; ++i) {
-        if (wm + C::WM * i >= nsub) continue;
-        const int rbase = 32 * (wm + C::WM * i) + 4 * khalf;
-        if (C::SWIGLU) {
-            constexpr int H = C::TN / 2;
+        for (int i = 0; i < TA; ++i) {
+            const int rbase = 32 * (wm + C::WM * i) + 4 * khalf;
+            if (C::SWIGLU) {
+                constexpr int H = C::TN / 2;
 #pragma unroll
-            for (int j = 0; j < H; ++j) {
-                const int col = n0 + 32 * (wn * H + j) + col_in;
+                for (int j = 0; j < H; ++j) {
+                    const int col = n0 + 32 * (wn * H + j) + col_in;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = rbase + 8 * (r / 4) + (r % 4);
-                    if (row < tile_rows && col < N) {
-                        const float g = acc[i][j][r], u = acc[i][j + H][r];
-                        Cout[(size_t)(row0 + row) * N + col] = (bf16_t)(silu_f32(g) * u);
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = rbase + 8 * (r / 4) + (r % 4);
+                        if (row < tile_rows && col < N) {
+                            const float g = acc[i][j][r], u = acc[i][j + H][r];
+                            Cout[(size_t)(row0 + row) * N + col] = (bf16_t)(silu_f32(g) * u);
+                        }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j) {
+                    const int col = n0 + 32 * (wn * C::TN + j) + col_in;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = rbase + 8 * (r / 4) + (r % 4);
+                        if (row < tile_rows && col < N)
+                            Cout[(size_t)(row0 + row) * N + col] = (bf16_t)acc[i][j][r];
                     }
                 }
             }
-        } else {
-#pragma unroll
-            for (int j = 0; j < C::TN; ++j) {
-                const int col = n0 + 32 * (wn * C::TN + j) + col_in;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = rbase + 8 * (r / 4) + (r % 4);
-                    if (row < tile_rows && col < N)
-                        Cout[(size_t)(row0 + row) * N + col] = (bf16_t)acc[i][j][r];
-                }
-            }
         }
+    };
+
+    static_assert(C::TM <= 4, "extend the dispatch below");
+    switch (ta) {
+        case 0: run(std::integral_constant<int, 0>{}); break;
+        case 1: run(std::integral_constant<int, 1>{}); break;
+        case 2: if constexpr (C::TM >= 2) run(std::integral_constant<int, 2>{}); break;
+        case 3: if constexpr (C::TM >= 3) run(std::integral_constant<int, 3>{}); break;
+        default: if constexpr (C::TM >= 4) run(std::integral_constant<int, 4>{}); break;
     }
 }
 
