@@ -298,7 +298,7 @@ hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, c
                                  hipStream_t s) {
     if (n_rows == 0) return hipSuccess;
     if (large_batch(n_rows, E))
-        return launch_one<TileCfg<256, 256, 2, 4, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s);
+        return launch_expert_up_bf16_large(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s);
     return launch_one<TileCfg<64, 128, 1, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s);
 }
 
@@ -306,7 +306,7 @@ hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, cons
                                    int n_rows, int d, int f, int E, bf16_t* y, hipStream_t s) {
     if (n_rows == 0) return hipSuccess;
     if (large_batch(n_rows, E))
-        return launch_one<TileCfg<256, 256, 2, 4, false>>(h, offsets, wd, nullptr, n_rows, E, d, f, y, s);
+        return launch_expert_down_bf16_large(h, offsets, wd, n_rows, d, f, E, y, s);
     return launch_one<TileCfg<64, 64, 1, 2, false>>(h, offsets, wd, nullptr, n_rows, E, d, f, y, s);
 }
 

@@ -1,0 +1,56 @@
+// Device-side map from a workgroup id to its (expert, n-tile, m-tile) for the grouped expert
+// GEMMs.  m-tiles never straddle experts; the map is computed from expert_offsets on the
+// device so that no host read-back sits between the permutation and the GEMM.
+//
+// XCD awareness: the hardware deals workgroup ids round-robin to the 8 accelerator dies
+// (id % 8), each with its own L2.  Logical tiles are ordered expert-major, then n-tile, then
+// m-tile, and die x takes the x-th contiguous eighth of that order: the m-tiles that share a
+// weight tile, and the n-tiles that share an activation tile, run on one die at about the
+// same time and meet in its L2.
+#pragma once
+#include "common.h"
+
+namespace specmoe {
+
+struct TileLoc {
+    int expert;      // expert id
+    int row0;        // first row of the tile in the permuted row space
+    int tile_rows;   // valid rows in the tile (1 .. BM)
+    int nt;          // n-tile index
+};
+
+template <int BM>
+__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets, int E, int NT,
+                                            unsigned block_id, TileLoc& t) {
+    int total_mt = 0;
+    for (int e = 0; e < E; ++e) total_mt += (offsets[e + 1] - offsets[e] + BM - 1) / BM;
+    const long long G = (long long)total_mt * NT;
+    const long long per_xcd = (G + kXcds - 1) / kXcds;
+    const long long slot = block_id / kXcds;
+    const long long L = (long long)(block_id % kXcds) * per_xcd + slot;
+    if (slot >= per_xcd || L >= G) return false;
+    long long base = 0;
+    for (int e = 0; e < E; ++e) {
+        const int lo = offsets[e], hi = offsets[e + 1];
+        const int mt = (hi - lo + BM - 1) / BM;
+        if (L < base + (long long)mt * NT) {
+            const long long rem = L - base;
+            t.nt = (int)(rem / mt);
+            const int mi = (int)(rem - (long long)t.nt * mt);
+            t.expert = e;
+            t.row0 = lo + mi * BM;
+            t.tile_rows = min(BM, hi - t.row0);
+            return true;
+        }
+        base += (long long)mt * NT;
+    }
+    return false;
+}
+
+// Upper bound of the grid (host side): sum_e ceil(M_e/BM) <= floor(n_rows/BM) + E.
+inline long long grid_upper_bound(int n_rows, int E, int BM, long long NT) {
+    long long g = ((long long)(n_rows / BM) + E) * NT;
+    return (g + kXcds - 1) / kXcds * kXcds;
+}
+
+}  // namespace specmoe
