@@ -37,9 +37,10 @@ struct PipeCfg {
     static constexpr int ROW_BYTES = BK * 2, CHUNKS = BK / 8;        // 16-byte chunks per row
     static constexpr int RPG = 16 / CHUNKS;          // tile rows per sweep over the 16 bank groups
     static constexpr int ROWS_PER_DMA = 1024 / ROW_BYTES;            // rows one wave-load fills
-    static constexpr int A_PW = BM / ROWS_PER_DMA / NWAVES;          // wave-loads per wave, A
+    static constexpr int A_LOADS = BM / ROWS_PER_DMA;                // wave-loads per stage, A
+    static constexpr int A_PW = (A_LOADS + NWAVES - 1) / NWAVES;     // at most, per wave
     static constexpr int B_PW = BN / ROWS_PER_DMA / NWAVES;          // wave-loads per wave, B
-    static constexpr int G = A_PW + B_PW;                            // loads per thread per stage
+    static constexpr int G_MAX = A_PW + B_PW;                        // loads per wave per stage
     static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;
@@ -47,11 +48,11 @@ struct PipeCfg {
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(KK % 2 == 0, "fragment double buffer needs an even number of k-steps");
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "tile / wave grid mismatch");
-    static_assert(BM % (ROWS_PER_DMA * NWAVES) == 0 && BN % (ROWS_PER_DMA * NWAVES) == 0,
+    static_assert(BM % ROWS_PER_DMA == 0 && BN % (ROWS_PER_DMA * NWAVES) == 0,
                   "wave-loads must divide evenly");
     static_assert(!SWIGLU || ((BN / 2 / ROWS_PER_DMA) % NWAVES == 0 && TN % 2 == 0),
                   "gate/up halves must split on a wave-load round and pair up inside a wave");
-    static_assert(STAGES >= 3 && (STAGES - 3) * G <= 63, "ring depth");
+    static_assert(STAGES >= 3 && (STAGES - 3) * G_MAX <= 15, "ring depth");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
@@ -71,9 +72,24 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
+// s_waitcnt takes an immediate; n is wave-uniform and constant over the k loop
+__device__ __forceinline__ void wait_vmcnt_dyn(int n) {
+    switch (n) {
+        case 0: wait_vmcnt<0>(); break;   case 1: wait_vmcnt<1>(); break;
+        case 2: wait_vmcnt<2>(); break;   case 3: wait_vmcnt<3>(); break;
+        case 4: wait_vmcnt<4>(); break;   case 5: wait_vmcnt<5>(); break;
+        case 6: wait_vmcnt<6>(); break;   case 7: wait_vmcnt<7>(); break;
+        case 8: wait_vmcnt<8>(); break;   case 9: wait_vmcnt<9>(); break;
+        case 10: wait_vmcnt<10>(); break; case 11: wait_vmcnt<11>(); break;
+        case 12: wait_vmcnt<12>(); break; case 13: wait_vmcnt<13>(); break;
+        case 14: wait_vmcnt<14>(); break; default: wait_vmcnt<15>(); break;
+    }
+}
 
-// PROBE is 0 in the library.  The tuning harness instantiates 1 (matrix instructions
-// removed) and 2 (global->LDS loads removed) to time the two halves of the pipeline alone.
+// PROBE is 0 in the library.  The tuning harness sets bits to time parts of the pipeline
+// alone: 1 = no matrix instructions, 2 = no global->LDS loads in the loop, 4 = no barrier,
+// 8 = no fragment reads in the loop, 16 = no A loads, 32 = no B loads.  Results are
+// meaningless then; only the time counts.
 template <typename C, int PROBE = 0>
 __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
     const bf16_t* __restrict__ A,        // [n_rows, K]
@@ -85,7 +101,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
 
     const int NT = (N + C::BN_OUT - 1) / C::BN_OUT;
     TileLoc t;
-    if (!locate_tile<C::BM>(offsets, E, NT, blockIdx.x, t)) return;
+    if (!locate_tile_even<C::BM>(offsets, E, NT, blockIdx.x, t)) return;
     const int row0 = t.row0, tile_rows = t.tile_rows;
     const int n0 = t.nt * C::BN_OUT;
     const int nsub = (tile_rows + 31) / 32;
@@ -104,6 +120,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
                                         : nullptr;
     const int n_left = N - n0;
     uint32_t a_off[C::A_PW], b_off[C::B_PW];
+    int a_cnt = 0;                               // A wave-loads this wave issues per stage
     {
         const int srow = lane / C::CHUNKS, pc = lane % C::CHUNKS;   // LDS slot of this lane
 #pragma unroll
@@ -111,6 +128,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
             const int r = (wave + jj * C::NWAVES) * C::ROWS_PER_DMA + srow;
             const int c = pc ^ ((r / C::RPG) % C::CHUNKS);
             a_off[jj] = (uint32_t)((min(r, tile_rows - 1) * K + c * 8) * 2);
+            // this wave's A loads: wave-load j = wave + jj*NWAVES covers tile rows j*16.. ;
+            // only loads that hold at least one real row are issued
+            if ((wave + jj * C::NWAVES) * C::ROWS_PER_DMA < tile_rows) a_cnt = jj + 1;
         }
 #pragma unroll
         for (int jj = 0; jj < C::B_PW; ++jj) {
@@ -132,14 +152,14 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
         kq = kq >= KT ? kq - KT : kq;
         const size_t kb = (size_t)kq * C::ROW_BYTES;
         const uint32_t sbase = lds_base + (uint32_t)buf * C::STAGE_BYTES + wave * 1024u;
-        if (PROBE == 2 && kt >= C::STAGES - 1) return;
+        if ((PROBE & 2) && kt >= C::STAGES - 1) return;
 #pragma unroll
         for (int jj = 0; jj < C::A_PW; ++jj)
-            dma16(a_base + kb, a_off[jj], sbase + jj * C::NWAVES * 1024u);
+            if (jj < a_cnt && !(PROBE & 16)) dma16(a_base + kb, a_off[jj], sbase + jj * C::NWAVES * 1024u);
 #pragma unroll
         for (int jj = 0; jj < C::B_PW; ++jj) {
             const bool up = C::SWIGLU && (jj * C::NWAVES * C::ROWS_PER_DMA >= C::BN / 2);
-            dma16((up ? w1 : w0) + kb, b_off[jj], sbase + C::A_BYTES + jj * C::NWAVES * 1024u);
+            if (!(PROBE & 32)) dma16((up ? w1 : w0) + kb, b_off[jj], sbase + C::A_BYTES + jj * C::NWAVES * 1024u);
         }
     };
 
@@ -163,6 +183,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
     };
 
     const int ta = min(C::TM, max(0, (nsub - wm + C::WM - 1) / C::WM));   // active sub-tiles
+    // loads this wave has in flight per stage; stages STAGES-3 deep may still be outstanding
+    // when the stage needed next must have landed
+    const int vm_allow = (C::STAGES - 3) * (a_cnt + C::B_PW);
 
     auto run = [&](auto ta_tag) __attribute__((always_inline)) {
         constexpr int TA = decltype(ta_tag)::value;
@@ -176,8 +199,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
         bf16x8 af[2][TAX], bfr[2][C::TN];
-        auto read_frags = [&](int set, int buf, int kk) __attribute__((always_inline)) {
+        auto read_frags = [&](int set, int buf, int kk, bool in_loop) __attribute__((always_inline)) {
             if (TA == 0) return;
+            if ((PROBE & 8) && in_loop) return;
             const unsigned char* sb = lds_raw + buf * C::STAGE_BYTES;
 #pragma unroll
             for (int j = 0; j < C::TN; ++j)
@@ -188,7 +212,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
                                                                32 * C::WM * i * C::ROW_BYTES);
         };
         auto mfma_set = [&](int set) __attribute__((always_inline)) {
-            if (PROBE == 1) {                      // keep the fragment reads alive, no MFMA
+            if (PROBE & 1) {                       // keep the fragment reads alive, no MFMA
 #pragma unroll
                 for (int i = 0; i < TA; ++i)
                     asm volatile("" :: "v"(af[set][i]));
@@ -201,16 +225,17 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
             for (int i = 0; i < TA; ++i)
 #pragma unroll
                 for (int j = 0; j < C::TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j],
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i],
                                                                         acc[i][j], 0, 0, 0);
         };
 
         // prologue: request stages 0 .. STAGES-2, wait for 0 and 1
 #pragma unroll
         for (int s = 0; s < C::STAGES - 1; ++s) issue_stage(s, s);
-        wait_vmcnt<(C::STAGES - 3) * C::G>();
+        wait_vmcnt_dyn(vm_allow);
         __builtin_amdgcn_s_barrier();
-        read_frags(0, 0, 0);
+        read_frags(0, 0, 0, false);
+        if (PROBE & 8) read_frags(1, 0, 1, false);
 
         int buf = 0;                               // ring slot of stage kt
         for (int kt = 0; kt < KT; ++kt) {
@@ -219,62 +244,67 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
             issue_stage(kt + C::STAGES - 1, buf_free);
 #pragma unroll
             for (int kk = 0; kk < C::KK; ++kk) {
-                if (kk + 1 < C::KK) read_frags((kk + 1) & 1, buf, kk + 1);
-                else read_frags(0, buf_next, 0);   // stage kt+1 landed one step ago
+                if (kk + 1 < C::KK) read_frags((kk + 1) & 1, buf, kk + 1, true);
+                else read_frags(0, buf_next, 0, true);   // stage kt+1 landed one step ago
                 // the scheduler must not sink the next k-step's fragment reads below the
                 // matrix instructions they are meant to overlap with
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_set(kk & 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            wait_vmcnt<(C::STAGES - 3) * C::G>();  // own share of stage kt+2 has landed
-            __builtin_amdgcn_s_barrier();
+            wait_vmcnt_dyn(vm_allow);              // own share of stage kt+2 has landed
+            if (!(PROBE & 4)) __builtin_amdgcn_s_barrier();
             buf = buf_next;
         }
         wait_vmcnt<0>();                           // no load may outlive the workgroup's LDS
 
-        // epilogue: accumulator element r of a lane is row 8*(r/4) + 4*(lane/32) + r%4,
-        // column lane%32 of its 32x32 sub-tile
-        const int col_in = lane & 31, khalf = lane >> 5;
+        // epilogue.  The matrix instruction is issued as (weights x activations^T), so a lane
+        // holds ONE tile row (lane%32) and, for each g = r/4, four consecutive output columns
+        // 8g + 4*(lane/32) + r%4: one 8-byte store per g, no transposition through LDS.
+        const int row = lane & 31, chalf = (lane >> 5) * 4;
 #pragma unroll
         for (int i = 0; i < TA; ++i) {
-            const int rbase = 32 * (wm + C::WM * i) + 4 * khalf;
-            if (C::SWIGLU) {
-                constexpr int H = C::TN / 2;
+            const int trow = 32 * (wm + C::WM * i) + row;
+            if (trow >= tile_rows) continue;
+            bf16_t* crow = Cout + (size_t)(row0 + trow) * N;
+            constexpr int JN = C::SWIGLU ? C::TN / 2 : C::TN;
 #pragma unroll
-                for (int j = 0; j < H; ++j) {
-                    const int col = n0 + 32 * (wn * H + j) + col_in;
+            for (int j = 0; j < JN; ++j) {
+                const int cbase = n0 + 32 * (wn * JN + j) + chalf;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = rbase + 8 * (r / 4) + (r % 4);
-                        if (row < tile_rows && col < N) {
-                            const float g = acc[i][j][r], u = acc[i][j + H][r];
-                            Cout[(size_t)(row0 + row) * N + col] = (bf16_t)(silu_f32(g) * u);
+                for (int g = 0; g < 4; ++g) {
+                    const int col = cbase + 8 * g;
+                    float v[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (C::SWIGLU) {
+                            const float gt = acc[i][j][4 * g + q], up = acc[i][j + JN][4 * g + q];
+                            v[q] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up;
+                        } else {
+                            v[q] = acc[i][j][4 * g + q];
                         }
                     }
-                }
-            } else {
+                    if (col + 3 < N) {
+                        uint2 pk = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                        *reinterpret_cast<uint2*>(crow + col) = pk;
+                    } else {
 #pragma unroll
-                for (int j = 0; j < C::TN; ++j) {
-                    const int col = n0 + 32 * (wn * C::TN + j) + col_in;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = rbase + 8 * (r / 4) + (r % 4);
-                        if (row < tile_rows && col < N)
-                            Cout[(size_t)(row0 + row) * N + col] = (bf16_t)acc[i][j][r];
+                        for (int q = 0; q < 4; ++q)
+                            if (col + q < N) crow[col + q] = (bf16_t)v[q];
                     }
                 }
             }
         }
     };
 
-    static_assert(C::TM <= 4, "extend the dispatch below");
+    static_assert(C::TM <= 5, "extend the dispatch below");
     switch (ta) {
         case 0: run(std::integral_constant<int, 0>{}); break;
         case 1: run(std::integral_constant<int, 1>{}); break;
         case 2: if constexpr (C::TM >= 2) run(std::integral_constant<int, 2>{}); break;
         case 3: if constexpr (C::TM >= 3) run(std::integral_constant<int, 3>{}); break;
-        default: if constexpr (C::TM >= 4) run(std::integral_constant<int, 4>{}); break;
+        case 4: if constexpr (C::TM >= 4) run(std::integral_constant<int, 4>{}); break;
+        default: if constexpr (C::TM >= 5) run(std::integral_constant<int, 5>{}); break;
     }
 }
 
@@ -302,14 +332,14 @@ hipError_t launch_pipe(const bf16_t* A, const int32_t* offsets, const bf16_t* W0
 hipError_t launch_expert_up_bf16_large(const bf16_t* x_perm, const int32_t* offsets,
                                        const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
                                        int f, int E, bf16_t* h, hipStream_t s) {
-    return launch_pipe<PipeCfg<256, 256, 32, 4, 2, 4, true>>(x_perm, offsets, wg, wu, n_rows, E, f,
+    return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, true, 4>>(x_perm, offsets, wg, wu, n_rows, E, f,
                                                              d, h, s);
 }
 
 hipError_t launch_expert_down_bf16_large(const bf16_t* h, const int32_t* offsets,
                                          const bf16_t* wd, int n_rows, int d, int f, int E,
                                          bf16_t* y, hipStream_t s) {
-    return launch_pipe<PipeCfg<256, 256, 32, 4, 2, 4, false>>(h, offsets, wd, nullptr, n_rows, E,
+    return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, false, 4>>(h, offsets, wd, nullptr, n_rows, E,
                                                               d, f, y, s);
 }
 

@@ -47,6 +47,51 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets,
     return false;
 }
 
+// Even split: an expert with M rows gets ceil(M / BM_MAX) m-tiles of equal height (rounded up
+// to the 32-row MFMA granule), so no tile is a thin remainder that would stream a whole
+// weight tile for a handful of rows.
+struct EvenSplit {
+    int mt;    // m-tiles of the expert
+    int rpt;   // rows per tile (multiple of 32, <= BM_MAX); the last tile may hold fewer
+};
+template <int BM_MAX>
+__device__ __forceinline__ EvenSplit even_split(int M) {
+    EvenSplit s{0, 0};
+    if (M <= 0) return s;
+    const int mt0 = (M + BM_MAX - 1) / BM_MAX;
+    s.rpt = ((M + mt0 - 1) / mt0 + 31) / 32 * 32;
+    s.mt = (M + s.rpt - 1) / s.rpt;
+    return s;
+}
+
+template <int BM_MAX>
+__device__ __forceinline__ bool locate_tile_even(const int32_t* __restrict__ offsets, int E,
+                                                 int NT, unsigned block_id, TileLoc& t) {
+    int total_mt = 0;
+    for (int e = 0; e < E; ++e) total_mt += even_split<BM_MAX>(offsets[e + 1] - offsets[e]).mt;
+    const long long G = (long long)total_mt * NT;
+    const long long per_xcd = (G + kXcds - 1) / kXcds;
+    const long long slot = block_id / kXcds;
+    const long long L = (long long)(block_id % kXcds) * per_xcd + slot;
+    if (slot >= per_xcd || L >= G) return false;
+    long long base = 0;
+    for (int e = 0; e < E; ++e) {
+        const int lo = offsets[e], hi = offsets[e + 1];
+        const EvenSplit sp = even_split<BM_MAX>(hi - lo);
+        if (L < base + (long long)sp.mt * NT) {
+            const long long rem = L - base;
+            t.nt = (int)(rem / sp.mt);
+            const int mi = (int)(rem - (long long)t.nt * sp.mt);
+            t.expert = e;
+            t.row0 = lo + mi * sp.rpt;
+            t.tile_rows = min(sp.rpt, hi - t.row0);
+            return true;
+        }
+        base += (long long)sp.mt * NT;
+    }
+    return false;
+}
+
 // Upper bound of the grid (host side): sum_e ceil(M_e/BM) <= floor(n_rows/BM) + E.
 inline long long grid_upper_bound(int n_rows, int E, int BM, long long NT) {
     long long g = ((long long)(n_rows / BM) + E) * NT;
