@@ -16,6 +16,7 @@ namespace {
 
 constexpr int kPermWaves = 8;
 constexpr int kPermThreads = kPermWaves * kWave;
+constexpr int kBatch = 8;          // index rows fetched ahead per wavefront
 
 __global__ __launch_bounds__(kPermThreads) void permute_index_kernel(
     const int32_t* __restrict__ idx, int P, int E, int32_t* __restrict__ offsets,
@@ -34,9 +35,17 @@ __global__ __launch_bounds__(kPermThreads) void permute_index_kernel(
     const int lo = min(P, wave * per_wave), hi = min(P, lo + per_wave);
     int* mine = wave_cnt + wave * E;
 
-    for (int p = lo + lane; p < hi; p += kWave) {                       // (A)
-        int e = min(max(idx[p], 0), E - 1);
-        atomicAdd(&mine[e], 1);
+    // (A) counts.  Indices are fetched kBatch wavefront-rows at a time so the loads overlap.
+    for (int base = lo; base < hi; base += kWave * kBatch) {
+        int ev[kBatch];
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            const int p = base + b * kWave + lane;
+            ev[b] = (p < hi) ? idx[p] : -1;
+        }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b)
+            if (base + b * kWave + lane < hi) atomicAdd(&mine[min(max(ev[b], 0), E - 1)], 1);
     }
     __syncthreads();
 
@@ -76,23 +85,32 @@ __global__ __launch_bounds__(kPermThreads) void permute_index_kernel(
     __syncthreads();
 
     const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
-    for (int base = lo; base < hi; base += kWave) {                     // (C)
-        const int p = base + lane;
-        const bool valid = p < hi;
-        const int e = valid ? min(max(idx[p], 0), E - 1) : -1;
-        unsigned long long todo = __ballot(valid);
-        int dest = 0;
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const int cur = __shfl(e, leader, kWave);
-            const unsigned long long grp = __ballot(e == cur);
-            if (e == cur) dest = mine[cur] + __popcll(grp & lt_mask);
-            __builtin_amdgcn_wave_barrier();
-            if (lane == leader) mine[cur] += __popcll(grp);
-            __builtin_amdgcn_wave_barrier();
-            todo &= ~grp;
+    for (int base0 = lo; base0 < hi; base0 += kWave * kBatch) {         // (C)
+        int ev[kBatch];
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            const int p = base0 + b * kWave + lane;
+            ev[b] = (p < hi) ? min(max(idx[p], 0), E - 1) : -1;
         }
-        if (valid) { row_src[dest] = p; row_of[p] = dest; }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            const int p = base0 + b * kWave + lane;
+            const bool valid = p < hi;
+            const int e = ev[b];
+            unsigned long long todo = __ballot(valid);
+            int dest = 0;
+            while (todo) {
+                const int leader = __ffsll((long long)todo) - 1;
+                const int cur = __shfl(e, leader, kWave);
+                const unsigned long long grp = __ballot(e == cur);
+                if (e == cur) dest = mine[cur] + __popcll(grp & lt_mask);
+                __builtin_amdgcn_wave_barrier();
+                if (lane == leader) mine[cur] += __popcll(grp);
+                __builtin_amdgcn_wave_barrier();
+                todo &= ~grp;
+            }
+            if (valid) { row_src[dest] = p; row_of[p] = dest; }
+        }
     }
 }
 

@@ -1,99 +1,124 @@
 // Gate of one MoE block: router logits in fp64, top-k on logits, softmax gate weights.
 // (SpecMoE Sec. 2.1: the gate selects the top-K experts per token.)
 //
-// One 64-lane wavefront owns one token.  Lanes stride the d_model axis with 16-byte loads,
-// every expert column goes through the same lane partition and the same xor-butterfly, so two
-// experts with identical router rows produce bit-identical logits and the tie is decided by
-// expert id.  The E logits of the token live in LDS; top-k is k rounds of a wave-wide arg-max
-// on the key (logit descending, expert id ascending).
+// A workgroup of 4 wavefronts owns TOK tokens.  The d_model axis is dealt to the 256 lanes in
+// 16-byte chunks (chunk q -> wave (q/64)%4, lane q%64), every lane keeps fp64 partial sums
+// for TOK tokens x 8 experts, so one router-weight load feeds TOK tokens.  Partial sums are
+// reduced with the same xor-butterfly and the same wave order for every expert column: two
+// experts with identical router rows get bit-identical logits and the tie goes to the lower
+// id.  Wave t then ranks token t: the E logits sit in LDS, top-k is k rounds of a wave-wide
+// arg-max on the key (logit descending, expert id ascending).
 #include "common.h"
 
 namespace specmoe {
 namespace {
 
-constexpr int kRouteWaves = 4;      // tokens per workgroup
-constexpr int kExpertChunk = 8;     // expert columns accumulated per pass over x[t,:]
+constexpr int kRouteWaves = 4;
+constexpr int kRouteThreads = kRouteWaves * kWave;
+constexpr int kExpertChunk = 8;     // expert columns accumulated per pass over x
 
-template <typename T> struct Vec;
-template <> struct Vec<float> {
+template <typename T, bool VEC> struct Chunk;
+template <> struct Chunk<float, true> {
     static constexpr int N = 4;
-    __device__ static void load(const float* p, double (&o)[4]) {
-        float4 v = *reinterpret_cast<const float4*>(p);
-        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    typedef U128 Raw;
+    __device__ static Raw load(const float* p) { return *reinterpret_cast<const U128*>(p); }
+    __device__ static void widen(Raw v, double (&o)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = (double)__uint_as_float(v[i]);
     }
 };
-template <> struct Vec<bf16_t> {
+template <> struct Chunk<bf16_t, true> {
     static constexpr int N = 8;
-    __device__ static void load(const bf16_t* p, double (&o)[8]) {
-        U128 v = *reinterpret_cast<const U128*>(p);
-        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    typedef U128 Raw;
+    __device__ static Raw load(const bf16_t* p) { return *reinterpret_cast<const U128*>(p); }
+    __device__ static void widen(Raw v, double (&o)[8]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            o[2 * i] = (double)bf16_bits_to_float(w[i] & 0xffffu);
-            o[2 * i + 1] = (double)bf16_bits_to_float(w[i] >> 16);
+            o[2 * i] = (double)bf16_bits_to_float(v[i] & 0xffffu);
+            o[2 * i + 1] = (double)bf16_bits_to_float(v[i] >> 16);
         }
     }
+};
+template <typename T> struct Chunk<T, false> {          // any d_model, any alignment
+    static constexpr int N = 1;
+    typedef float Raw;
+    __device__ static Raw load(const T* p) { return load_as_float(p); }
+    __device__ static void widen(Raw v, double (&o)[1]) { o[0] = (double)v; }
 };
 
 __device__ __forceinline__ bool better(double av, int aid, double bv, int bid) {
     return (av > bv) || (av == bv && aid < bid);
 }
 
-template <typename T>
-__global__ __launch_bounds__(kRouteWaves* kWave) void route_topk_kernel(
+template <typename T, bool VEC, int TOK>
+__global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
     const T* __restrict__ x, const T* __restrict__ wr, const float* __restrict__ bias, int Tn,
-    int d, int E, int k, int renorm, int vec_ok_i, int32_t* __restrict__ idx_out,
-    float* __restrict__ w_out) {
-    extern __shared__ double lds_logits[];   // [kRouteWaves][E]
+    int d, int E, int k, int renorm, int32_t* __restrict__ idx_out, float* __restrict__ w_out) {
+    extern __shared__ double lds_d[];                 // logits[TOK][E], then part[4][TOK][8]
+    double* logits = lds_d;
+    double* part = lds_d + (size_t)TOK * E;
+    typedef Chunk<T, VEC> CH;
+    constexpr int V = CH::N;
     const int lane = threadIdx.x % kWave;
-    const int wave = threadIdx.x / kWave;
-    const int t = blockIdx.x * kRouteWaves + wave;
-    if (t >= Tn) return;                     // whole wave leaves; no block-wide barrier below
-    double* logit = lds_logits + (size_t)wave * E;
-    const T* xt = x + (size_t)t * d;
-    constexpr int V = Vec<T>::N;
-    const bool vec_ok = vec_ok_i != 0;     // host checked: d % V == 0 and 16-byte aligned bases
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int t0 = blockIdx.x * TOK;
+    const int nq = d / V;                             // chunks per row (VEC: d % V == 0)
 
     for (int e0 = 0; e0 < E; e0 += kExpertChunk) {
-        double acc[kExpertChunk];
+        double acc[TOK][kExpertChunk];
 #pragma unroll
-        for (int c = 0; c < kExpertChunk; ++c) acc[c] = 0.0;
-        if (vec_ok) {
-            for (int j = lane * V; j < d; j += kWave * V) {
-                double xv[V];
-                Vec<T>::load(xt + j, xv);
+        for (int t = 0; t < TOK; ++t)
 #pragma unroll
-                for (int c = 0; c < kExpertChunk; ++c) {
-                    if (e0 + c < E) {
-                        double wv[V];
-                        Vec<T>::load(wr + (size_t)(e0 + c) * d + j, wv);
+            for (int c = 0; c < kExpertChunk; ++c) acc[t][c] = 0.0;
+        for (int q = threadIdx.x; q < nq; q += kRouteThreads) {
+            typename CH::Raw xr[TOK], wraw[kExpertChunk];
 #pragma unroll
-                        for (int i = 0; i < V; ++i) acc[c] = fma(xv[i], wv[i], acc[c]);
-                    }
-                }
-            }
-        } else {
-            for (int j = lane; j < d; j += kWave) {
-                double xv = (double)load_as_float(xt + j);
+            for (int t = 0; t < TOK; ++t)
+                xr[t] = CH::load(x + (size_t)min(t0 + t, Tn - 1) * d + (size_t)q * V);
 #pragma unroll
-                for (int c = 0; c < kExpertChunk; ++c)
-                    if (e0 + c < E)
-                        acc[c] = fma(xv, (double)load_as_float(wr + (size_t)(e0 + c) * d + j), acc[c]);
+            for (int c = 0; c < kExpertChunk; ++c)
+                wraw[c] = CH::load(wr + (size_t)min(e0 + c, E - 1) * d + (size_t)q * V);
+            double xv[TOK][V];
+#pragma unroll
+            for (int t = 0; t < TOK; ++t) CH::widen(xr[t], xv[t]);
+#pragma unroll
+            for (int c = 0; c < kExpertChunk; ++c) {
+                double wv[V];
+                CH::widen(wraw[c], wv);
+#pragma unroll
+                for (int t = 0; t < TOK; ++t)
+#pragma unroll
+                    for (int i = 0; i < V; ++i) acc[t][c] = fma(xv[t][i], wv[i], acc[t][c]);
             }
         }
+        // lanes -> wave total (butterfly), waves -> workgroup total (fixed order 0,1,2,3)
 #pragma unroll
-        for (int c = 0; c < kExpertChunk; ++c) {
-            double s = wave_sum(acc[c]);
-            if (lane == 0 && e0 + c < E)
-                logit[e0 + c] = s + (bias ? (double)bias[e0 + c] : 0.0);
+        for (int t = 0; t < TOK; ++t)
+#pragma unroll
+            for (int c = 0; c < kExpertChunk; ++c) {
+                const double s = wave_sum(acc[t][c]);
+                if (lane == 0) part[(wave * TOK + t) * kExpertChunk + c] = s;
+            }
+        __syncthreads();
+        for (int i = threadIdx.x; i < TOK * kExpertChunk; i += kRouteThreads) {
+            const int t = i / kExpertChunk, c = i % kExpertChunk;
+            if (e0 + c < E) {
+                double s = part[(0 * TOK + t) * kExpertChunk + c];
+#pragma unroll
+                for (int w = 1; w < kRouteWaves; ++w) s += part[(w * TOK + t) * kExpertChunk + c];
+                logits[(size_t)t * E + e0 + c] = s + (bias ? (double)bias[e0 + c] : 0.0);
+            }
         }
+        __syncthreads();
     }
-    __builtin_amdgcn_wave_barrier();
-    __threadfence_block();
 
+    // wave t ranks token t0 + t (TOK <= 4 waves)
+    if (wave >= TOK || t0 + wave >= Tn) return;
+    const int t = t0 + wave;
+    const double* logit = logits + (size_t)wave * E;
     // lane owns experts lane, lane+64, ...; `taken` marks the ones already selected.
     // Lane s keeps the result of round s (k <= 64), so the final stores are coalesced.
-    constexpr int kOwn = 1024 / kWave;       // SPECMOE_MAX_EXPERTS / 64
+    constexpr int kOwn = 1024 / kWave;                // SPECMOE_MAX_EXPERTS / 64
     uint32_t taken = 0;
     double vmax = 0.0, denom = 1.0, wsum_sel = 0.0, my_p = 0.0;
     int my_id = 0;
@@ -117,12 +142,12 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_topk_kernel(
         if (s == 0) {
             // softmax denominator over all E experts, relative to the largest logit
             vmax = bv;
-            double part = 0.0;
-            for (int e = lane; e < E; e += kWave) part += exp(logit[e] - vmax);
-            denom = wave_sum(part);
+            double p = 0.0;
+            for (int e = lane; e < E; e += kWave) p += exp(logit[e] - vmax);
+            denom = wave_sum(p);
         }
         double p = exp(bv - vmax) / denom;
-        wsum_sel += p;                        // slot order, identical on every lane
+        wsum_sel += p;                                // slot order, identical on every lane
         if (lane == s) { my_p = p; my_id = bid; }
     }
     if (lane < k) {
@@ -131,23 +156,35 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_topk_kernel(
     }
 }
 
+template <typename T, bool VEC, int TOK>
+void launch_variant(const T* x, const T* wr, const float* bias, int Tn, int d, int E, int k,
+                    int renorm, int32_t* idx, float* w, hipStream_t s) {
+    dim3 grid((Tn + TOK - 1) / TOK), block(kRouteThreads);
+    size_t lds = ((size_t)TOK * E + (size_t)kRouteWaves * TOK * kExpertChunk) * sizeof(double);
+    hipLaunchKernelGGL((route_topk_kernel<T, VEC, TOK>), grid, block, lds, s, x, wr, bias, Tn, d,
+                       E, k, renorm, idx, w);
+}
+
+template <typename T, int V>
+void launch_typed(const void* x, const void* wr, const float* bias, int Tn, int d, int E, int k,
+                  int renorm, int32_t* idx, float* w, hipStream_t s) {
+    const bool vec = (d % V == 0) && ((((uintptr_t)x | (uintptr_t)wr) & 15u) == 0);
+    const bool many = Tn >= 1024;                     // enough tokens to fill the chip 4 at a time
+    const T* xt = (const T*)x;
+    const T* wt = (const T*)wr;
+    if (vec && many) launch_variant<T, true, 4>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, s);
+    else if (vec) launch_variant<T, true, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, s);
+    else launch_variant<T, false, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, s);
+}
+
 }  // namespace
 
 hipError_t launch_route_topk(const void* x, const void* wr, const float* bias, int T, int d,
                              int E, int k, int renorm, int dtype, int32_t* idx, float* w,
                              hipStream_t s) {
     if (T == 0) return hipSuccess;
-    dim3 grid((T + kRouteWaves - 1) / kRouteWaves), block(kRouteWaves * kWave);
-    size_t lds = (size_t)kRouteWaves * E * sizeof(double);
-    const bool aligned = (((uintptr_t)x | (uintptr_t)wr) & 15u) == 0;
-    if (dtype == 0)
-        hipLaunchKernelGGL(route_topk_kernel<float>, grid, block, lds, s, (const float*)x,
-                           (const float*)wr, bias, T, d, E, k, renorm,
-                           (int)(aligned && d % Vec<float>::N == 0), idx, w);
-    else
-        hipLaunchKernelGGL(route_topk_kernel<bf16_t>, grid, block, lds, s, (const bf16_t*)x,
-                           (const bf16_t*)wr, bias, T, d, E, k, renorm,
-                           (int)(aligned && d % Vec<bf16_t>::N == 0), idx, w);
+    if (dtype == 0) launch_typed<float, 4>(x, wr, bias, T, d, E, k, renorm, idx, w, s);
+    else launch_typed<bf16_t, 8>(x, wr, bias, T, d, E, k, renorm, idx, w, s);
     return hipGetLastError();
 }
 
