@@ -28,7 +28,8 @@ namespace {
 
 template <int BM_, int BN_, int BK_, int STAGES_, int WM_, int WN_, bool SWIGLU_, int KROT_ = 0>
 struct PipeCfg {
-    static constexpr int KROT = KROT_;               // k-loop rotation per n-tile, in steps
+    static constexpr int KROT = KROT_ % 1000;        // k-loop rotation per n-tile, in steps
+    static constexpr bool SPREAD = KROT_ < 1000;     // tuning switch: spread the wave-loads
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_, WM = WM_, WN = WN_;
     static constexpr bool SWIGLU = SWIGLU_;
     static constexpr int NWAVES = WM * WN, THREADS = NWAVES * kWave;
@@ -108,7 +109,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int wm = wave % C::WM, wn = wave / C::WM;
+    // Waves w and w+4 share a SIMD.  Giving them different wm means a tile with an odd number
+    // of 32-row sub-tiles loads every SIMD equally (5+4 instead of 5+5 and 4+4).
+    const int wm = wave / C::WN, wn = wave % C::WN;
     const uint32_t lds_base =
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_raw;
 
@@ -147,20 +150,28 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
     // channels in lockstep.  The k loop is therefore rotated by an amount that depends on the
     // n-tile only (m-tiles sharing a weight tile stay aligned and still meet in L2).
     const int kt0 = (int)(((long long)t.nt * C::KROT) % KT);
-    auto issue_stage = [&](int kt, int buf) __attribute__((always_inline)) {
+    // One wave-load of stage kt into ring slot buf.  Loads 0 .. A_PW-1 are this wave's A rows
+    // (issued only if they hold real rows), loads A_PW .. A_PW+B_PW-1 its weight rows.
+    auto issue_one = [&](int which, int kt, int buf) __attribute__((always_inline)) {
+        if ((PROBE & 2) && kt >= C::STAGES - 1) return;
         int kq = min(kt, KT - 1) + kt0;                             // clamped: tail re-loads
         kq = kq >= KT ? kq - KT : kq;
         const size_t kb = (size_t)kq * C::ROW_BYTES;
         const uint32_t sbase = lds_base + (uint32_t)buf * C::STAGE_BYTES + wave * 1024u;
-        if ((PROBE & 2) && kt >= C::STAGES - 1) return;
 #pragma unroll
         for (int jj = 0; jj < C::A_PW; ++jj)
-            if (jj < a_cnt && !(PROBE & 16)) dma16(a_base + kb, a_off[jj], sbase + jj * C::NWAVES * 1024u);
+            if (which == jj && jj < a_cnt && !(PROBE & 16))
+                dma16(a_base + kb, a_off[jj], sbase + jj * C::NWAVES * 1024u);
 #pragma unroll
         for (int jj = 0; jj < C::B_PW; ++jj) {
             const bool up = C::SWIGLU && (jj * C::NWAVES * C::ROWS_PER_DMA >= C::BN / 2);
-            if (!(PROBE & 32)) dma16((up ? w1 : w0) + kb, b_off[jj], sbase + C::A_BYTES + jj * C::NWAVES * 1024u);
+            if (which == C::A_PW + jj && !(PROBE & 32))
+                dma16((up ? w1 : w0) + kb, b_off[jj], sbase + C::A_BYTES + jj * C::NWAVES * 1024u);
         }
+    };
+    auto issue_stage = [&](int kt, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < C::G_MAX; ++q) issue_one(q, kt, buf);
     };
 
     // ---- LDS side of the fragment reads ---------------------------------------------------
@@ -211,18 +222,14 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
                 af[set][i] = *reinterpret_cast<const bf16x8*>(sb + a_rd[kk] +
                                                                32 * C::WM * i * C::ROW_BYTES);
         };
-        auto mfma_set = [&](int set) __attribute__((always_inline)) {
+        auto mfma_row = [&](int set, int i) __attribute__((always_inline)) {
             if (PROBE & 1) {                       // keep the fragment reads alive, no MFMA
-#pragma unroll
-                for (int i = 0; i < TA; ++i)
-                    asm volatile("" :: "v"(af[set][i]));
+                asm volatile("" :: "v"(af[set][i]));
 #pragma unroll
                 for (int j = 0; j < C::TN; ++j)
                     asm volatile("" :: "v"(bfr[set][j]));
                 return;
             }
-#pragma unroll
-            for (int i = 0; i < TA; ++i)
 #pragma unroll
                 for (int j = 0; j < C::TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i],
@@ -241,16 +248,33 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
         for (int kt = 0; kt < KT; ++kt) {
             const int buf_next = (buf + 1 == C::STAGES) ? 0 : buf + 1;
             const int buf_free = (buf == 0) ? C::STAGES - 1 : buf - 1;   // held stage kt-1
-            issue_stage(kt + C::STAGES - 1, buf_free);
+            // The requests for stage kt+STAGES-1 go out one at a time between the matrix
+            // instructions of the first k-step (all eight waves leave the barrier together; a
+            // burst of wave-loads would back up the address unit and hold the MFMAs behind it).
+            // sched_barrier(0) pins this order: the compiler's scheduler would otherwise sink
+            // the fragment reads next to their use and bunch the loads.
 #pragma unroll
             for (int kk = 0; kk < C::KK; ++kk) {
                 if (kk + 1 < C::KK) read_frags((kk + 1) & 1, buf, kk + 1, true);
                 else read_frags(0, buf_next, 0, true);   // stage kt+1 landed one step ago
-                // the scheduler must not sink the next k-step's fragment reads below the
-                // matrix instructions they are meant to overlap with
                 __builtin_amdgcn_sched_barrier(0);
-                mfma_set(kk & 1);
-                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < TAX; ++i) {
+                    if (i < TA) mfma_row(kk & 1, i);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (kk == 0) {
+                        if (C::SPREAD) {
+                            if (i < C::G_MAX) issue_one(i, kt + C::STAGES - 1, buf_free);
+                            if (i == TAX - 1)
+#pragma unroll
+                                for (int q = TAX; q < C::G_MAX; ++q)
+                                    issue_one(q, kt + C::STAGES - 1, buf_free);
+                        } else if (i == 0) {
+                            issue_stage(kt + C::STAGES - 1, buf_free);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
             }
             wait_vmcnt_dyn(vm_allow);              // own share of stage kt+2 has landed
             if (!(PROBE & 4)) __builtin_amdgcn_s_barrier();
@@ -332,14 +356,14 @@ hipError_t launch_pipe(const bf16_t* A, const int32_t* offsets, const bf16_t* W0
 hipError_t launch_expert_up_bf16_large(const bf16_t* x_perm, const int32_t* offsets,
                                        const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
                                        int f, int E, bf16_t* h, hipStream_t s) {
-    return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, true, 4>>(x_perm, offsets, wg, wu, n_rows, E, f,
+    return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, true>>(x_perm, offsets, wg, wu, n_rows, E, f,
                                                              d, h, s);
 }
 
 hipError_t launch_expert_down_bf16_large(const bf16_t* h, const int32_t* offsets,
                                          const bf16_t* wd, int n_rows, int d, int f, int E,
                                          bf16_t* y, hipStream_t s) {
-    return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, false, 4>>(h, offsets, wd, nullptr, n_rows, E,
+    return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, false>>(h, offsets, wd, nullptr, n_rows, E,
                                                               d, f, y, s);
 }
 
