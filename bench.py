@@ -165,9 +165,11 @@ def main():
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
         dst = torch.empty_like(src)
+        flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()   # evicts src
+        torch.cuda.synchronize()
         dst.copy_(src)
         torch.cuda.synchronize()
-        del src, dst
+        del src, dst, flush
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, L, draft, target)
     print(json.dumps(out))

@@ -1,0 +1,49 @@
+"""Why the floating-point parity bar is measured per output row against the row's largest
+magnitude.  A CPU model of the rounding points any bf16 matrix-core implementation has (h
+rounded to bf16 before the second contraction, y_perm and out rounded to bf16 once each)
+applied to the ORACLE's own fp64 intermediates: it shows the error level the arithmetic
+itself allows, independent of any kernel."""
+import numpy as np
+import torch
+
+from oracle import moe_verify_oracle as orc
+from workloads.metrics import floored_rel_err
+
+
+def _bf16(a):
+    return torch.from_numpy(np.asarray(a, dtype=np.float64)).to(torch.float32).to(torch.bfloat16) \
+        .to(torch.float64).numpy()
+
+
+def _row_err(got, want):
+    return float((np.abs(got - want).max(axis=1) / np.abs(want).max(axis=1)).max())
+
+
+def test_mandatory_bf16_roundings_fit_row_norm_bar_but_not_elementwise_floor():
+    rng = np.random.default_rng(0)
+    T, d, f, E, k = 96, 512, 1024, 4, 2
+    x = _bf16(rng.normal(size=(T, d)) / np.sqrt(d))
+    wr = _bf16(rng.normal(size=(E, d)) * 0.02)
+    wg = _bf16(rng.normal(size=(E, f, d)) * 0.02)
+    wu = _bf16(rng.normal(size=(E, f, d)) * 0.02)
+    wd = _bf16(rng.normal(size=(E, d, f)) * 0.02)
+    want = orc.moe_layer_brute_force(x, wr, wg, wu, wd, k)
+
+    idx, w, _ = orc.route_topk(x, wr, k)
+    got = np.zeros_like(want)
+    for t in range(T):
+        acc = np.zeros(d)
+        for s in range(k):
+            e = idx[t, s]
+            h = _bf16(orc.silu(wg[e] @ x[t]) * (wu[e] @ x[t]))       # rounding point 1
+            y = _bf16(wd[e] @ h)                                     # rounding point 2
+            acc += np.float32(w[t, s]) * y
+        got[t] = _bf16(acc)                                          # rounding point 3
+    row = _row_err(got, want)
+    elem = floored_rel_err(got, want, floor_frac=1e-3)
+    print(f"ideal bf16 pipeline: per-row err {row:.2e}, floored element-wise err {elem:.2e}")
+    # the per-row max-norm error of an ideal implementation sits below the 1e-2 bar ...
+    assert row < 1e-2, row
+    # ... while element-wise relative error with a floor at 1e-3 of the tensor maximum is
+    # already beyond 1e-2 for it: small elements inherit the absolute rounding error of h.
+    assert elem > 1e-2, elem
