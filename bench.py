@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4])
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--seed", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -89,19 +89,33 @@ def main():
     sm.load_library()
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
-    L = synth.make_layer(cfg, "cuda", seed=args.seed)
+    stacked = cfg.n_layers > 1
+    if stacked:
+        x0, layers = synth.make_stack(cfg, "cuda", seed=args.seed)
+        L = dict(layers[0], x=x0)
+    else:
+        L = synth.make_layer(cfg, "cuda", seed=args.seed)
     draft, target = synth.make_tokens(cfg, seed=args.seed)
     draft_d, target_d = draft.cuda(), target.cuda()
     alen = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
     toks = torch.empty(cfg.B, cfg.gamma + 1, dtype=torch.int32, device="cuda")
-    layer = sm.MoEVerifyLayer(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
-                              renorm=cfg.renorm)
     stream = torch.cuda.current_stream()
+    if stacked:
+        stack = sm.MoEVerifyStack(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
+                                  renorm=cfg.renorm)
+        layer = stack.layer
 
-    def step(ev=None):
-        layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
-                      stream=stream, up_events=ev)
-        sm.spec_accept(draft_d, target_d, alen, toks, stream)
+        def step(ev=None):
+            stack.forward(x0, layers, stream=stream, up_events=ev)
+            sm.spec_accept(draft_d, target_d, alen, toks, stream)
+    else:
+        layer = sm.MoEVerifyLayer(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
+                                  renorm=cfg.renorm)
+
+        def step(ev=None):
+            layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
+                          stream=stream, up_events=ev)
+            sm.spec_accept(draft_d, target_d, alen, toks, stream)
 
     for _ in range(args.warmup):
         step()
@@ -121,7 +135,7 @@ def main():
     esize = 4 if cfg.dtype == "f32" else 2
     P, d, f = cfg.P, cfg.d_model, cfg.d_ff
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
-    tflops = cfg.flops() / (ms_per_step * 1e-3) / 1e12
+    tflops = cfg.flops() * cfg.n_layers / (ms_per_step * 1e-3) / 1e12
 
     # dominant kernel: the gate/up expert GEMM with the SwiGLU epilogue (2/3 of the flops)
     up_flops = 4.0 * P * d * f
@@ -162,6 +176,11 @@ def main():
         "tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else None,
         "roofline": roof,
     }
+    if stacked:
+        out["config"]["layers"] = cfg.n_layers
+        out["accepted_tokens_per_s"] = float(alen.sum().item()) / (ms_per_step * 1e-3)
+        out["mean_accept_len"] = float(alen.float().mean().item())
+        args.no_cpu_baseline = True      # the bounded oracle sample is defined for one layer
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
         dst = torch.empty_like(src)

@@ -5,4 +5,4 @@ from .binding import (  # noqa: F401
     moe_grouped_swiglu_workspace_bytes, moe_permute, moe_rmsnorm, moe_route_topk, spec_accept,
     status_string, EXPORTED_SYMBOLS,
 )
-from .layer import MoEVerifyLayer  # noqa: F401
+from .layer import MoEVerifyLayer, MoEVerifyStack  # noqa: F401

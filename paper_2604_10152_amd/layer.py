@@ -45,3 +45,35 @@ class MoEVerifyLayer:
         B.moe_expert_down(self.h, self.expert_offsets, w_down, self.y_perm, stream)
         B.moe_combine(self.y_perm, self.row_of, self.topk_w, residual, out, stream)
         return out
+
+
+class MoEVerifyStack:
+    """n_layers x [RMSNorm -> MoE verify layer -> residual add] on one set of shared buffers.
+
+    h_0 = x;  h_{l+1} = h_l + MoE_l(RMSNorm_l(h_l)).  The residual add is fused into
+    moe_combine.  Layer weights stay resident in HBM (lists of per-layer tensors).
+    """
+
+    def __init__(self, T, d_model, d_ff, E, k, dtype, device="cuda", renorm=True, eps=1e-5):
+        self.layer = MoEVerifyLayer(T, d_model, d_ff, E, k, dtype, device, renorm)
+        self.eps = eps
+        dev = torch.device(device)
+        self.normed = torch.empty((T, d_model), dtype=dtype, device=dev)
+        self.h = [torch.empty((T, d_model), dtype=dtype, device=dev) for _ in range(2)]
+
+    def forward(self, x, layers, keep_hidden=False, stream=None, up_events=None):
+        """`layers`: list of dicts with gain, w_router, bias, w_gate, w_up, w_down.
+        Returns the final hidden state (and, if keep_hidden, clones of every h_l).
+        `up_events` brackets the gate/up expert GEMM of the first layer (benchmark only)."""
+        hidden = [x.clone()] if keep_hidden else None
+        cur = x
+        for li, L in enumerate(layers):
+            nxt = self.h[li % 2]
+            B.moe_rmsnorm(cur, L["gain"], self.eps, self.normed, stream)
+            self.layer.forward(self.normed, L["w_router"], L["w_gate"], L["w_up"], L["w_down"],
+                               L.get("bias"), residual=cur, out=nxt, stream=stream,
+                               up_events=up_events if li == 0 else None)
+            cur = nxt
+            if keep_hidden:
+                hidden.append(cur.clone())
+        return (cur, hidden) if keep_hidden else cur

@@ -367,3 +367,57 @@ def test_identical_experts_invariant_on_gpu():
     layer, out = _run_layer(cfg, L)
     want = orc.expert_ffn(f64(L["x"]), f64(L["w_gate"][0]), f64(L["w_up"][0]), f64(L["w_down"][0]))
     assert row_rel_err(f64(out), want) <= TOL[torch.bfloat16]
+
+
+# ------------------------------------------------------------------ multi-layer stack (cfg 5)
+def _check_stack(cfg, n_layers, n_sample, seed):
+    """Every layer of the stack is checked on its own: the oracle gets the GPU's input h_l of
+    that layer (exact bf16 values), so routing is compared bit-exactly layer by layer and the
+    outputs h_{l+1} to the single-layer bar.  (Comparing only the end of a 32-layer chain would
+    mix in discrete routing flips of near-tie tokens caused by earlier bf16 roundings.)"""
+    x, layers = synth.make_stack(cfg, "cuda", seed=seed, n_layers=n_layers)
+    stack = sm.MoEVerifyStack(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
+                              renorm=cfg.renorm)
+    out, hidden = stack.forward(x, layers, keep_hidden=True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    rng = np.random.default_rng(seed)
+    sample = np.sort(rng.choice(cfg.T, size=n_sample, replace=False))
+    sel = torch.from_numpy(sample).cuda()
+    worst = 0.0
+    for l, L in enumerate(layers):
+        h_in = f64(hidden[l][sel])
+        lay = dict(gain=f64(L["gain"]), w_router=f64(L["w_router"]), bias=None,
+                   w_gate=LazyF64(L["w_gate"]), w_up=LazyF64(L["w_up"]), w_down=LazyF64(L["w_down"]))
+        want = orc.decoder_stack(h_in, [lay], cfg.k, cfg.renorm)
+        got = f64(hidden[l + 1][sel])
+        # the residual dominates h; judge the layer on what it ADDED, against that increment
+        inc_err = row_rel_err(got - h_in, want - h_in)
+        worst = max(worst, inc_err)
+        print(f"   layer {l}: increment err {inc_err:.3e}", flush=True)
+        # rounding h_{l+1} to bf16 costs up to 2^-9 of |h|, which may exceed 1e-2 of the increment
+        ulp_floor = float((np.abs(want).max(axis=1) * 2.0 ** -8 / np.abs(want - h_in).max(axis=1)).max())
+        assert inc_err <= TOL[cfg.torch_dtype] + ulp_floor, (l, inc_err, ulp_floor)
+        assert row_rel_err(got, want) <= TOL[cfg.torch_dtype]
+    return worst
+
+
+def test_stack_three_layers_full_width():
+    cfg = synth.CONFIGS[5]
+    _say("stack cfg5 shape, 3 layers, 8 sampled tokens")
+    _check_stack(cfg, n_layers=3, n_sample=8, seed=5)
+
+
+def test_stack_small_fp32_all_tokens():
+    _say("stack fp32 small, 4 layers")
+    cfg = synth.MoEConfig("stack-f32", "f32", 96, 160, 6, 2, 5, 3, 1.0, 0.05, 0.3, n_layers=4)
+    _check_stack(cfg, n_layers=4, n_sample=cfg.T, seed=6)
+
+
+@pytest.mark.skipif(os.environ.get("SPECMOE_FULL_STACK", "0") != "1",
+                    reason="32 resident layers = 90 GB of weights and ~2 min of oracle work; "
+                           "set SPECMOE_FULL_STACK=1 to run")
+def test_stack_full_32_layers_one_token():
+    cfg = synth.CONFIGS[5]
+    _say("stack cfg5 full: 32 layers, 1 sampled token")
+    _check_stack(cfg, n_layers=32, n_sample=1, seed=5)

@@ -113,6 +113,20 @@ def make_layer(cfg: MoEConfig, device="cpu", seed=0, layer=0, T=None):
     return out
 
 
+def make_stack(cfg: MoEConfig, device="cpu", seed=0, n_layers=None):
+    """Per-layer tensors of the multi-layer configuration (gain = 1 + small noise, bf16/f32)."""
+    n_layers = cfg.n_layers if n_layers is None else n_layers
+    layers = []
+    for l in range(n_layers):
+        L = make_layer(cfg, device, seed, layer=l + 1, T=1)
+        del L["x"]
+        g = _gen("cpu", 1000 * int(seed) + 10 * (l + 1) + 6)
+        L["gain"] = (1.0 + 0.05 * torch.randn(cfg.d_model, generator=g)).to(cfg.torch_dtype).to(device)
+        layers.append(L)
+    x = _normal((cfg.T, cfg.d_model), 1.0, cfg.torch_dtype, device, 1000 * int(seed) + 7)
+    return x, layers
+
+
 def make_tokens(cfg: MoEConfig, seed=0, B=None, gamma=None):
     """Draft ids [B,gamma] and target ids [B,gamma+1], int32, on the CPU.
 
