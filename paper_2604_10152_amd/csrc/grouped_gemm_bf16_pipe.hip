@@ -46,14 +46,14 @@ struct PipeCfg {
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;
     static constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
-    static_assert(BK == 32 || BK == 64, "BK");
+    static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
     static_assert(KK % 2 == 0, "fragment double buffer needs an even number of k-steps");
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "tile / wave grid mismatch");
     static_assert(BM % ROWS_PER_DMA == 0 && BN % (ROWS_PER_DMA * NWAVES) == 0,
                   "wave-loads must divide evenly");
     static_assert(!SWIGLU || ((BN / 2 / ROWS_PER_DMA) % NWAVES == 0 && TN % 2 == 0),
                   "gate/up halves must split on a wave-load round and pair up inside a wave");
-    static_assert(STAGES >= 3 && (STAGES - 3) * G_MAX <= 15, "ring depth");
+    static_assert(STAGES >= 3 && (STAGES - 3) * G_MAX <= 63, "ring depth (vmcnt is 6 bits)");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
@@ -79,16 +79,16 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 // s_waitcnt takes an immediate; n is wave-uniform and constant over the k loop
 __device__ __forceinline__ void wait_vmcnt_dyn(int n) {
+#define SPECMOE_W4(b) case b: wait_vmcnt<b>(); break; case b + 1: wait_vmcnt<b + 1>(); break; \
+                      case b + 2: wait_vmcnt<b + 2>(); break; case b + 3: wait_vmcnt<b + 3>(); break;
     switch (n) {
-        case 0: wait_vmcnt<0>(); break;   case 1: wait_vmcnt<1>(); break;
-        case 2: wait_vmcnt<2>(); break;   case 3: wait_vmcnt<3>(); break;
-        case 4: wait_vmcnt<4>(); break;   case 5: wait_vmcnt<5>(); break;
-        case 6: wait_vmcnt<6>(); break;   case 7: wait_vmcnt<7>(); break;
-        case 8: wait_vmcnt<8>(); break;   case 9: wait_vmcnt<9>(); break;
-        case 10: wait_vmcnt<10>(); break; case 11: wait_vmcnt<11>(); break;
-        case 12: wait_vmcnt<12>(); break; case 13: wait_vmcnt<13>(); break;
-        case 14: wait_vmcnt<14>(); break; default: wait_vmcnt<15>(); break;
+        SPECMOE_W4(0) SPECMOE_W4(4) SPECMOE_W4(8) SPECMOE_W4(12) SPECMOE_W4(16) SPECMOE_W4(20)
+        SPECMOE_W4(24) SPECMOE_W4(28) SPECMOE_W4(32) SPECMOE_W4(36) SPECMOE_W4(40) SPECMOE_W4(44)
+        SPECMOE_W4(48) SPECMOE_W4(52) SPECMOE_W4(56)
+        case 60: wait_vmcnt<60>(); break; case 61: wait_vmcnt<61>(); break;
+        case 62: wait_vmcnt<62>(); break; default: wait_vmcnt<63>(); break;
     }
+#undef SPECMOE_W4
 }
 
 // PROBE is 0 in the library.  The tuning harness sets bits to time parts of the pipeline
@@ -404,6 +404,23 @@ hipError_t launch_expert_down_bf16_large(const bf16_t* h, const int32_t* offsets
                                          const bf16_t* wd, int n_rows, int d, int f, int E,
                                          bf16_t* y, hipStream_t s) {
     return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, false>>(h, offsets, wd, nullptr, n_rows, E,
+                                                              d, f, y, s);
+}
+
+// Few rows per expert: the weights stream from HBM once and nothing else matters.  64-row
+// tiles, narrow N so that every CU owns a stream, 128-byte rows per step (BK = 64; 64-byte rows
+// lose ~10 % of HBM throughput) and a 4 / 6 stage ring (~70-120 KB of requests in flight per CU).
+hipError_t launch_expert_up_bf16_small(const bf16_t* x_perm, const int32_t* offsets,
+                                       const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
+                                       int f, int E, bf16_t* h, hipStream_t s) {
+    return launch_pipe<PipeCfg<64, 128, 64, 4, 1, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f,
+                                                            d, h, s);
+}
+
+hipError_t launch_expert_down_bf16_small(const bf16_t* h, const int32_t* offsets,
+                                         const bf16_t* wd, int n_rows, int d, int f, int E,
+                                         bf16_t* y, hipStream_t s) {
+    return launch_pipe<PipeCfg<64, 128, 64, 6, 1, 4, false>>(h, offsets, wd, nullptr, n_rows, E,
                                                               d, f, y, s);
 }
 

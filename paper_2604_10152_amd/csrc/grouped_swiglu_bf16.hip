@@ -19,6 +19,7 @@
 // take sub-tiles interleaved so that a partial tile stays balanced across the SIMDs.
 #include "common.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace specmoe {
@@ -289,6 +290,17 @@ hipError_t launch_one(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
 }  // namespace
 
 static inline bool large_batch(int n_rows, int E) { return (long long)n_rows >= 128ll * E; }
+// Few rows per expert, two kernels: with a long contraction axis the deep global->LDS ring wins
+// (5.8 vs 5.3 TB/s at the Mixtral shape); with a short one (fine-grained experts) a tile lives
+// for a few dozen steps only and three co-resident register-staged workgroups per CU hide the
+// prologue / epilogue of each other better (360 vs 490 us at the 64-expert shape).
+constexpr int kLongK = 4096;
+// tuning switch (environment): SPECMOE_REGSTAGED=1 selects the register-staged small-batch kernels
+static inline bool use_regstaged() {
+    static int v = -1;
+    if (v < 0) { const char* e = getenv("SPECMOE_REGSTAGED"); v = (e && e[0] == '1') ? 1 : 0; }
+    return v == 1;
+}
 
 // Large batches (>= 128 rows per expert on average): 256-row tiles, 8 wavefronts, MFMA-bound.
 // Few rows per expert: the weights stream once from HBM and narrow tiles give every CU its
@@ -299,6 +311,7 @@ hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, c
     if (n_rows == 0) return hipSuccess;
     if (large_batch(n_rows, E))
         return launch_expert_up_bf16_large(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s);
+    if (!use_regstaged() && d >= kLongK) return launch_expert_up_bf16_small(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s);
     return launch_one<TileCfg<64, 128, 1, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s);
 }
 
@@ -307,6 +320,7 @@ hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, cons
     if (n_rows == 0) return hipSuccess;
     if (large_batch(n_rows, E))
         return launch_expert_down_bf16_large(h, offsets, wd, n_rows, d, f, E, y, s);
+    if (!use_regstaged() && f >= kLongK) return launch_expert_down_bf16_small(h, offsets, wd, n_rows, d, f, E, y, s);
     return launch_one<TileCfg<64, 64, 1, 2, false>>(h, offsets, wd, nullptr, n_rows, E, d, f, y, s);
 }
 
