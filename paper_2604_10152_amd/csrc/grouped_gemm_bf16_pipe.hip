@@ -18,78 +18,14 @@
 // front of every LDS read that follows an LDS-DMA load, which collapses the ring to depth 1.
 // Hand-placed s_waitcnt vmcnt(n) is safe next to compiler-generated waits: extra outstanding
 // loads can only make a compiler-chosen wait stricter, never weaker.
-#include "common.h"
-#include "tile_map.h"
+#include "pipe_common.h"
 
 #include <type_traits>
 
 namespace specmoe {
 namespace {
 
-template <int BM_, int BN_, int BK_, int STAGES_, int WM_, int WN_, bool SWIGLU_, int KROT_ = 0>
-struct PipeCfg {
-    static constexpr int KROT = KROT_ % 1000;        // k-loop rotation per n-tile, in steps
-    static constexpr bool SPREAD = KROT_ < 1000;     // tuning switch: spread the wave-loads
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_, WM = WM_, WN = WN_;
-    static constexpr bool SWIGLU = SWIGLU_;
-    static constexpr int NWAVES = WM * WN, THREADS = NWAVES * kWave;
-    static constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);   // 32x32 sub-tiles per wave
-    static constexpr int KK = BK / 16;                               // MFMA k-steps per stage
-    static constexpr int ROW_BYTES = BK * 2, CHUNKS = BK / 8;        // 16-byte chunks per row
-    static constexpr int RPG = 16 / CHUNKS;          // tile rows per sweep over the 16 bank groups
-    static constexpr int ROWS_PER_DMA = 1024 / ROW_BYTES;            // rows one wave-load fills
-    static constexpr int A_LOADS = BM / ROWS_PER_DMA;                // wave-loads per stage, A
-    static constexpr int A_PW = (A_LOADS + NWAVES - 1) / NWAVES;     // at most, per wave
-    static constexpr int B_PW = BN / ROWS_PER_DMA / NWAVES;          // wave-loads per wave, B
-    static constexpr int G_MAX = A_PW + B_PW;                        // loads per wave per stage
-    static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
-    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;
-    static constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
-    static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
-    static_assert(KK % 2 == 0, "fragment double buffer needs an even number of k-steps");
-    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "tile / wave grid mismatch");
-    static_assert(BM % ROWS_PER_DMA == 0 && BN % (ROWS_PER_DMA * NWAVES) == 0,
-                  "wave-loads must divide evenly");
-    static_assert(!SWIGLU || ((BN / 2 / ROWS_PER_DMA) % NWAVES == 0 && TN % 2 == 0),
-                  "gate/up halves must split on a wave-load round and pair up inside a wave");
-    static_assert(STAGES >= 3 && (STAGES - 3) * G_MAX <= 63, "ring depth (vmcnt is 6 bits)");
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
-};
-
-// byte offset of 16-byte chunk c of tile row r: conflict-free for 128-bit accesses on the
-// 64-bank LDS (16 consecutive lanes = 16 consecutive rows must hit 16 different bank groups)
-template <typename C>
-__device__ __forceinline__ int swz(int r, int c) {
-    return r * C::ROW_BYTES + ((c ^ ((r / C::RPG) % C::CHUNKS)) << 4);
-}
-
-// Row pitch of the LDS image of a SwiGLU output tile (128 bf16 columns + 16 bytes of padding
-// so that the 8-byte accumulator stores of 32 consecutive rows spread over the banks).
-constexpr int kStageRowBytes = 128 * 2 + 16;
-
-// 64 lanes x 16 bytes: global (uniform base + per-lane byte offset) -> LDS [lds_addr, +1024)
-__device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
-// s_waitcnt takes an immediate; n is wave-uniform and constant over the k loop
-__device__ __forceinline__ void wait_vmcnt_dyn(int n) {
-#define SPECMOE_W4(b) case b: wait_vmcnt<b>(); break; case b + 1: wait_vmcnt<b + 1>(); break; \
-                      case b + 2: wait_vmcnt<b + 2>(); break; case b + 3: wait_vmcnt<b + 3>(); break;
-    switch (n) {
-        SPECMOE_W4(0) SPECMOE_W4(4) SPECMOE_W4(8) SPECMOE_W4(12) SPECMOE_W4(16) SPECMOE_W4(20)
-        SPECMOE_W4(24) SPECMOE_W4(28) SPECMOE_W4(32) SPECMOE_W4(36) SPECMOE_W4(40) SPECMOE_W4(44)
-        SPECMOE_W4(48) SPECMOE_W4(52) SPECMOE_W4(56)
-        case 60: wait_vmcnt<60>(); break; case 61: wait_vmcnt<61>(); break;
-        case 62: wait_vmcnt<62>(); break; default: wait_vmcnt<63>(); break;
-    }
-#undef SPECMOE_W4
-}
+using namespace pipe;
 
 // PROBE is 0 in the library.  The tuning harness sets bits to time parts of the pipeline
 // alone: 1 = no matrix instructions, 2 = no global->LDS loads in the loop, 4 = no barrier,
@@ -108,6 +44,8 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
     const int NT = (N + C::BN_OUT - 1) / C::BN_OUT;
     TileLoc t;
     if (!locate_tile_even<C::BM>(offsets, E, NT, blockIdx.x, t)) return;
+    long long probe_c0 = 0, probe_w0 = 0;
+    if (PROBE & 256) { probe_c0 = clock64(); probe_w0 = wall_clock64(); }
     const int row0 = t.row0, tile_rows = t.tile_rows;
     const int n0 = t.nt * C::BN_OUT;
     const int nsub = (tile_rows + 31) / 32;
@@ -350,6 +288,11 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
         default: if constexpr (C::TM >= 5) run(std::integral_constant<int, 5>{}); break;
     }
 
+    if ((PROBE & 256) && (blockIdx.x == 8 || blockIdx.x == 801) && threadIdx.x == 0) {
+        const long long dc = clock64() - probe_c0, dw = wall_clock64() - probe_w0;
+        printf("block %d: %lld core clk, %lld ref ticks -> %.0f MHz (if ref = 100 MHz)\n",
+               (int)blockIdx.x, dc, dw, (double)dc / (double)dw * 100.0);
+    }
     if (C::SWIGLU && !(PROBE & 64)) {
         // cooperative write-out of the staged tile: 16 bytes per lane, whole rows
         static_assert(!C::SWIGLU || (size_t)C::BM * kStageRowBytes <= C::LDS_BYTES, "stage tile");

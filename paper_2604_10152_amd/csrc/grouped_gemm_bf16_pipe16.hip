@@ -1,0 +1,303 @@
+// Large-batch expert GEMMs, v_mfma_f32_16x16x32_bf16 flavour of the pipelined kernel.
+// (SpecMoE Sec. 2.1 / 2.2: the rows routed to an expert meet its FFN-sized weights; at
+// verification time each expert sees hundreds of rows, so the contraction is MFMA-bound.)
+//
+// Same data movement as grouped_gemm_bf16_pipe.hip (global->LDS ring of BK = 32 stages, one
+// barrier per step, readiness one step ahead), different matrix instruction: one
+// 16x16x32 MFMA consumes a whole 64-byte tile row per lane, so a stage is ONE k-step.
+// Why this shape: under the chip's power limit the 16x16x32 instruction sustains ~13 % more
+// bf16 flops than 32x32x16 on the same operands (1.97 vs 1.75 PFLOP/s measured in a
+// register-only loop with changing operands), and its 16-row granule wastes fewer matrix
+// instructions on the ragged last rows of an expert.
+//
+// Software pipeline inside a stage: the wave's A sub-tiles form two groups.  Group 1's
+// fragments are read while group 0 multiplies; the next stage's B fragments and group 0 are
+// read while group 1 multiplies (the next stage landed one step ago).  B fragments alternate
+// between two register sets, hence the k loop is unrolled by two.
+#include "pipe_common.h"
+
+#include <type_traits>
+#include <utility>
+
+namespace specmoe {
+namespace {
+
+using namespace pipe;
+
+template <typename F, int... Is>
+__device__ __forceinline__ void dispatch_count(int n, F& f, std::integer_sequence<int, Is...>) {
+    ((n == Is ? (f(std::integral_constant<int, Is>{}), 0) : 0), ...);
+}
+
+template <typename C, int PROBE = 0>
+__global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
+    const bf16_t* __restrict__ A,        // [n_rows, K]
+    const int32_t* __restrict__ offsets, // [E+1]
+    const bf16_t* __restrict__ W0,       // [E, N, K]   (gate, or down)
+    const bf16_t* __restrict__ W1,       // [E, N, K]   (up; SWIGLU only)
+    int E, int N, int K, bf16_t* __restrict__ Cout /* [n_rows, N] */) {
+    static_assert(C::BK == 32, "a stage is exactly one 16x16x32 k-step");
+    constexpr int TM16 = C::BM / (16 * C::WM);       // 16-row A sub-tiles per wave
+    constexpr int TN16 = C::BN / (16 * C::WN);       // 16-col B sub-tiles per wave
+    constexpr int GA = (TM16 + 1) / 2;               // A sub-tiles per pipeline group
+    constexpr int A_SUB_BYTES = 16 * C::WM * C::ROW_BYTES;   // LDS distance of consecutive i
+    static_assert(!C::SWIGLU || TN16 % 2 == 0, "gate and up sub-tiles pair up inside a wave");
+    static_assert((16 * C::WM) % (C::RPG * C::CHUNKS) == 0, "sub-tile step must keep the swizzle");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
+
+    const int NT = (N + C::BN_OUT - 1) / C::BN_OUT;
+    TileLoc t;
+    if (!locate_tile_even<C::BM, 16>(offsets, E, NT, blockIdx.x, t)) return;
+    const int row0 = t.row0, tile_rows = t.tile_rows;
+    const int n0 = t.nt * C::BN_OUT;
+    const int nsub = (tile_rows + 15) / 16;
+
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    // waves w and w+4 share a SIMD: different wm keeps an odd sub-tile count balanced
+    const int wm = wave / C::WN, wn = wave % C::WN;
+    const uint32_t lds_base =
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_raw;
+
+    // ---- global side of the wave-loads (identical to the 32x32 kernel) --------------------
+    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(A + (size_t)row0 * K);
+    const size_t wrow = (size_t)t.expert * N + min(n0, N - 1);
+    const unsigned char* w0 = reinterpret_cast<const unsigned char*>(W0 + wrow * K);
+    const unsigned char* w1 = C::SWIGLU ? reinterpret_cast<const unsigned char*>(W1 + wrow * K)
+                                        : nullptr;
+    const int n_left = N - n0;
+    uint32_t a_off[C::A_PW], b_off[C::B_PW];
+    int a_cnt = 0;                               // A wave-loads this wave issues per stage
+    {
+        const int srow = lane / C::CHUNKS, pc = lane % C::CHUNKS;   // LDS slot of this lane
+#pragma unroll
+        for (int jj = 0; jj < C::A_PW; ++jj) {
+            const int r = (wave + jj * C::NWAVES) * C::ROWS_PER_DMA + srow;
+            const int c = pc ^ ((r / C::RPG) % C::CHUNKS);
+            a_off[jj] = (uint32_t)((min(r, tile_rows - 1) * K + c * 8) * 2);
+            if ((wave + jj * C::NWAVES) * C::ROWS_PER_DMA < tile_rows) a_cnt = jj + 1;
+        }
+#pragma unroll
+        for (int jj = 0; jj < C::B_PW; ++jj) {
+            const int r = (wave + jj * C::NWAVES) * C::ROWS_PER_DMA + srow;
+            const int c = pc ^ ((r / C::RPG) % C::CHUNKS);
+            const int rn = (C::SWIGLU && r >= C::BN / 2) ? r - C::BN / 2 : r;
+            b_off[jj] = (uint32_t)((min(rn, n_left - 1) * K + c * 8) * 2);
+        }
+    }
+    const int KT = K / C::BK;                    // even: the ABI requires K % 64 == 0
+    auto issue_one = [&](int which, int kt, int buf) __attribute__((always_inline)) {
+        if ((PROBE & 2) && kt >= C::STAGES - 1) return;
+        const size_t kb = (size_t)min(kt, KT - 1) * C::ROW_BYTES;   // clamped: tail re-loads
+        const uint32_t sbase = lds_base + (uint32_t)buf * C::STAGE_BYTES + wave * 1024u;
+#pragma unroll
+        for (int jj = 0; jj < C::A_PW; ++jj)
+            if (which == jj && jj < a_cnt)
+                dma16(a_base + kb, a_off[jj], sbase + jj * C::NWAVES * 1024u);
+#pragma unroll
+        for (int jj = 0; jj < C::B_PW; ++jj) {
+            const bool up = C::SWIGLU && (jj * C::NWAVES * C::ROWS_PER_DMA >= C::BN / 2);
+            if (which == C::A_PW + jj)
+                dma16((up ? w1 : w0) + kb, b_off[jj], sbase + C::A_BYTES + jj * C::NWAVES * 1024u);
+        }
+    };
+
+    // ---- LDS side: lane l reads row (l%16) of a sub-tile, 16-byte chunk l/16 -----------------
+    const int a_rd = swz<C>(16 * wm + (lane & 15), lane >> 4);
+    const int b_rd = C::A_BYTES + swz<C>(lane & 15, lane >> 4);
+    auto nb = [&](int j) __attribute__((always_inline)) -> int {     // B sub-tile base row
+        if (C::SWIGLU) {
+            constexpr int H = TN16 / 2;
+            return (j < H) ? 16 * (wn * H + j) : C::BN / 2 + 16 * (wn * H + (j - H));
+        }
+        return 16 * (wn * TN16 + j);
+    };
+
+    const int ta = min(TM16, max(0, (nsub - wm + C::WM - 1) / C::WM));   // active A sub-tiles
+    const int vm_allow = (C::STAGES - 3) * (a_cnt + C::B_PW);
+
+    auto run = [&](auto ta_tag) __attribute__((always_inline)) {
+        constexpr int TA = decltype(ta_tag)::value;
+        constexpr int TA0 = TA < GA ? TA : GA;        // active sub-tiles in group 0 / group 1
+        constexpr int TA1 = TA - TA0;
+        constexpr int TAX = TA > 0 ? TA : 1;
+        floatx4 acc[TAX][TN16];
+#pragma unroll
+        for (int i = 0; i < TA; ++i)
+#pragma unroll
+            for (int j = 0; j < TN16; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+
+        bf16x8 af[2][GA], bfr[2][TN16];
+        auto read_b = [&](int set, int buf) __attribute__((always_inline)) {
+            if (TA == 0) return;
+            const unsigned char* sb = lds_raw + buf * C::STAGE_BYTES + b_rd;
+#pragma unroll
+            for (int j = 0; j < TN16; ++j)
+                bfr[set][j] = *reinterpret_cast<const bf16x8*>(sb + nb(j) * C::ROW_BYTES);
+        };
+        auto read_a = [&](int grp, int buf) __attribute__((always_inline)) {
+            const unsigned char* sa = lds_raw + buf * C::STAGE_BYTES + a_rd + grp * GA * A_SUB_BYTES;
+#pragma unroll
+            for (int i = 0; i < GA; ++i)
+                if (i < (grp == 0 ? TA0 : TA1))
+                    af[grp][i] = *reinterpret_cast<const bf16x8*>(sa + i * A_SUB_BYTES);
+        };
+        // weights x activations^T: a lane ends up with ONE tile row (lane%16) and four
+        // consecutive output columns 4*(lane/16) + r of the 16x16 sub-tile
+        auto mfma_row = [&](int grp, int i, int bset) __attribute__((always_inline)) {
+            if (PROBE & 1) return;
+#pragma unroll
+            for (int j = 0; j < TN16; ++j)
+                acc[grp * GA + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    bfr[bset][j], af[grp][i], acc[grp * GA + i][j], 0, 0, 0);
+        };
+
+        // prologue: request stages 0 .. STAGES-2, wait for 0 and 1
+#pragma unroll
+        for (int s = 0; s < C::STAGES - 1; ++s)
+#pragma unroll
+            for (int q = 0; q < C::G_MAX; ++q) issue_one(q, s, s);
+        wait_vmcnt_dyn(vm_allow);
+        __builtin_amdgcn_s_barrier();
+        read_b(0, 0);
+        read_a(0, 0);
+
+        int buf = 0;                               // ring slot of the stage being multiplied
+        auto stage = [&](auto par_tag, int kt) __attribute__((always_inline)) {
+            constexpr int PAR = decltype(par_tag)::value;
+            const int buf_next = (buf + 1 == C::STAGES) ? 0 : buf + 1;
+            const int buf_free = (buf == 0) ? C::STAGES - 1 : buf - 1;   // held stage kt-1
+            read_a(1, buf);
+            // sched_barrier(0) pins the order: fragment reads stay ahead of the matrix
+            // instructions they overlap with, wave-loads go out one per sub-tile row
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < GA; ++i) {
+                if (i < TA0) mfma_row(0, i, PAR);
+                __builtin_amdgcn_sched_barrier(0);
+                if (i < C::G_MAX) issue_one(i, kt + C::STAGES - 1, buf_free);
+                if (i == GA - 1)
+#pragma unroll
+                    for (int q = GA; q < C::G_MAX; ++q) issue_one(q, kt + C::STAGES - 1, buf_free);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            read_b(PAR ^ 1, buf_next);             // stage kt+1 landed one step ago
+            read_a(0, buf_next);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < GA; ++i)
+                if (i < TA1) mfma_row(1, i, PAR);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_vmcnt_dyn(vm_allow);              // own share of stage kt+2 has landed
+            __builtin_amdgcn_s_barrier();
+            buf = buf_next;
+        };
+        for (int kt = 0; kt < KT; kt += 2) {
+            stage(std::integral_constant<int, 0>{}, kt);
+            stage(std::integral_constant<int, 1>{}, kt + 1);
+        }
+        wait_vmcnt<0>();                           // no load may outlive the workgroup's LDS
+
+        // epilogue: SwiGLU tiles are staged in LDS and written as whole rows by the workgroup,
+        // plain tiles go straight to global memory, 8 bytes (4 columns) per lane
+        const int mrow = lane & 15, cq = (lane >> 4) * 4;
+        if (C::SWIGLU) __builtin_amdgcn_s_barrier();   // every wave's loads have landed
+#pragma unroll
+        for (int i = 0; i < TA; ++i) {
+            const int trow = 16 * (wm + C::WM * i) + mrow;
+            if (!C::SWIGLU && trow >= tile_rows) continue;
+            bf16_t* crow = Cout + (size_t)(row0 + trow) * N;
+            constexpr int JN = C::SWIGLU ? TN16 / 2 : TN16;
+#pragma unroll
+            for (int j = 0; j < JN; ++j) {
+                const int ctile = 16 * (wn * JN + j) + cq;            // column inside the tile
+                float v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (C::SWIGLU) {
+                        const float gt = acc[i][j][q], up = acc[i][j + JN][q];
+                        v[q] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up;
+                    } else {
+                        v[q] = acc[i][j][q];
+                    }
+                }
+                const uint2 pk = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                if (C::SWIGLU) {
+                    *reinterpret_cast<uint2*>(lds_raw + trow * kStageRowBytes + ctile * 2) = pk;
+                } else {
+                    const int col = n0 + ctile;
+                    if (col + 3 < N) {
+                        *reinterpret_cast<uint2*>(crow + col) = pk;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (col + q < N) crow[col + q] = (bf16_t)v[q];
+                    }
+                }
+            }
+        }
+    };
+
+    dispatch_count(ta, run, std::make_integer_sequence<int, TM16 + 1>{});
+
+    if (C::SWIGLU) {
+        // cooperative write-out of the staged tile: 16 bytes per lane, whole rows
+        static_assert(!C::SWIGLU || (size_t)C::BM * kStageRowBytes <= C::LDS_BYTES, "stage tile");
+        static_assert(!C::SWIGLU || C::BN_OUT == 128, "stage row pitch assumes 128 columns");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        constexpr int CPR = C::BN_OUT / 8;                  // 16-byte chunks per tile row
+        constexpr int RPP = C::THREADS / CPR;               // rows per pass
+        const int cr = tid / CPR, cc = tid % CPR;
+        const int col = n0 + cc * 8;
+        for (int r = cr; r < tile_rows; r += RPP) {
+            const U128 v = *reinterpret_cast<const U128*>(lds_raw + r * kStageRowBytes + cc * 16);
+            bf16_t* dst = Cout + (size_t)(row0 + r) * N + col;
+            if (col + 7 < N) {
+                *reinterpret_cast<U128*>(dst) = v;
+            } else {
+                for (int q = 0; q < 8; ++q)
+                    if (col + q < N) dst[q] = reinterpret_cast<const bf16_t*>(&v)[q];
+            }
+        }
+    }
+}
+
+template <typename C>
+hipError_t launch_pipe16(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
+                         const bf16_t* W1, int n_rows, int E, int N, int K, bf16_t* Cout,
+                         hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&grouped_gemm_bf16_pipe16_kernel<C>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long long NT = (N + C::BN_OUT - 1) / C::BN_OUT;
+    const long long grid = grid_upper_bound(n_rows, E, C::BM, NT);
+    hipLaunchKernelGGL(grouped_gemm_bf16_pipe16_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS),
+                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_expert_up_bf16_large16(const bf16_t* x_perm, const int32_t* offsets,
+                                         const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
+                                         int f, int E, bf16_t* h, hipStream_t s) {
+    return launch_pipe16<PipeCfg<320, 256, 32, 4, 2, 4, true>>(x_perm, offsets, wg, wu, n_rows, E,
+                                                               f, d, h, s);
+}
+
+hipError_t launch_expert_down_bf16_large16(const bf16_t* h, const int32_t* offsets,
+                                           const bf16_t* wd, int n_rows, int d, int f, int E,
+                                           bf16_t* y, hipStream_t s) {
+    return launch_pipe16<PipeCfg<320, 256, 32, 4, 2, 4, false>>(h, offsets, wd, nullptr, n_rows, E,
+                                                                d, f, y, s);
+}
+
+}  // namespace specmoe

@@ -295,6 +295,12 @@ static inline bool large_batch(int n_rows, int E) { return (long long)n_rows >= 
 // for a few dozen steps only and three co-resident register-staged workgroups per CU hide the
 // prologue / epilogue of each other better (360 vs 490 us at the 64-expert shape).
 constexpr int kLongK = 4096;
+// tuning switch (environment): SPECMOE_MFMA32=1 selects the 32x32x16 large-batch kernels
+static inline bool use_mfma32() {
+    static int v = -1;
+    if (v < 0) { const char* e = getenv("SPECMOE_MFMA32"); v = (e && e[0] == '1') ? 1 : 0; }
+    return v == 1;
+}
 // tuning switch (environment): SPECMOE_REGSTAGED=1 selects the register-staged small-batch kernels
 static inline bool use_regstaged() {
     static int v = -1;
@@ -310,7 +316,8 @@ hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, c
                                  hipStream_t s) {
     if (n_rows == 0) return hipSuccess;
     if (large_batch(n_rows, E))
-        return launch_expert_up_bf16_large(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s);
+        return use_mfma32() ? launch_expert_up_bf16_large(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s)
+                            : launch_expert_up_bf16_large16(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s);
     if (!use_regstaged() && d >= kLongK) return launch_expert_up_bf16_small(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s);
     return launch_one<TileCfg<64, 128, 1, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s);
 }
@@ -319,7 +326,8 @@ hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, cons
                                    int n_rows, int d, int f, int E, bf16_t* y, hipStream_t s) {
     if (n_rows == 0) return hipSuccess;
     if (large_batch(n_rows, E))
-        return launch_expert_down_bf16_large(h, offsets, wd, n_rows, d, f, E, y, s);
+        return use_mfma32() ? launch_expert_down_bf16_large(h, offsets, wd, n_rows, d, f, E, y, s)
+                            : launch_expert_down_bf16_large16(h, offsets, wd, n_rows, d, f, E, y, s);
     if (!use_regstaged() && f >= kLongK) return launch_expert_down_bf16_small(h, offsets, wd, n_rows, d, f, E, y, s);
     return launch_one<TileCfg<64, 64, 1, 2, false>>(h, offsets, wd, nullptr, n_rows, E, d, f, y, s);
 }

@@ -52,23 +52,24 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets,
 // weight tile for a handful of rows.
 struct EvenSplit {
     int mt;    // m-tiles of the expert
-    int rpt;   // rows per tile (multiple of 32, <= BM_MAX); the last tile may hold fewer
+    int rpt;   // rows per tile (multiple of GRAN, <= BM_MAX); the last tile may hold fewer
 };
-template <int BM_MAX>
+template <int BM_MAX, int GRAN>
 __device__ __forceinline__ EvenSplit even_split(int M) {
     EvenSplit s{0, 0};
     if (M <= 0) return s;
     const int mt0 = (M + BM_MAX - 1) / BM_MAX;
-    s.rpt = ((M + mt0 - 1) / mt0 + 31) / 32 * 32;
+    s.rpt = ((M + mt0 - 1) / mt0 + GRAN - 1) / GRAN * GRAN;
     s.mt = (M + s.rpt - 1) / s.rpt;
     return s;
 }
 
-template <int BM_MAX>
+// GRAN = row granule of the matrix instruction in use (32 or 16)
+template <int BM_MAX, int GRAN = 32>
 __device__ __forceinline__ bool locate_tile_even(const int32_t* __restrict__ offsets, int E,
                                                  int NT, unsigned block_id, TileLoc& t) {
     int total_mt = 0;
-    for (int e = 0; e < E; ++e) total_mt += even_split<BM_MAX>(offsets[e + 1] - offsets[e]).mt;
+    for (int e = 0; e < E; ++e) total_mt += even_split<BM_MAX, GRAN>(offsets[e + 1] - offsets[e]).mt;
     const long long G = (long long)total_mt * NT;
     const long long per_xcd = (G + kXcds - 1) / kXcds;
     const long long slot = block_id / kXcds;
@@ -77,7 +78,7 @@ __device__ __forceinline__ bool locate_tile_even(const int32_t* __restrict__ off
     long long base = 0;
     for (int e = 0; e < E; ++e) {
         const int lo = offsets[e], hi = offsets[e + 1];
-        const EvenSplit sp = even_split<BM_MAX>(hi - lo);
+        const EvenSplit sp = even_split<BM_MAX, GRAN>(hi - lo);
         if (L < base + (long long)sp.mt * NT) {
             const long long rem = L - base;
             t.nt = (int)(rem / sp.mt);
