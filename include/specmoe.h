@@ -99,6 +99,16 @@ int moe_expert_up_swiglu(const void* x_perm, const int32_t* expert_offsets, cons
 int moe_expert_down(const void* h, const int32_t* expert_offsets, const void* w_down, int n_rows,
                     int d_model, int d_ff, int E, int dtype, void* y_perm, void* stream);
 
+/* moe_expert_up_swiglu with the row gather of moe_permute folded into its loads: row r of the
+ * (never materialised) x_perm is x[row_src[r] / k], x being the [T,d_model] token matrix.  Same
+ * result as moe_permute(x -> x_perm) followed by moe_expert_up_swiglu(x_perm); call
+ * moe_permute with x_perm = NULL to get the indices only.  n_rows <= T*k;
+ * T * d_model * sizeof(element) must stay below 4 GiB. */
+int moe_expert_up_swiglu_gather(const void* x, const int32_t* row_src, int T, int k,
+                                const int32_t* expert_offsets, const void* w_gate,
+                                const void* w_up, int n_rows, int d_model, int d_ff, int E,
+                                int dtype, void* h, void* stream);
+
 /* Gate-weighted mix of the selected experts' outputs (Sec. 2.1, Fig. 1b):
  *   out[t] = (residual ? residual[t] : 0) + sum_{s<k} topk_w[t,s] * y_perm[row_of[t*k+s]]
  * accumulated in fp32 in slot order, rounded once to `dtype`.  residual [T,d_model] in
@@ -115,6 +125,15 @@ int moe_combine(const void* y_perm, const int32_t* row_of, const float* topk_w,
  *   out_tokens[b,0..n_b] = target_ids[b,0..n_b], remaining entries -1.   gamma = 0 is legal. */
 int spec_accept(const int32_t* draft_ids, const int32_t* target_ids, int B, int gamma,
                 int32_t* accept_len, int32_t* out_tokens, void* stream);
+
+/* Temporally hot experts of the block (Sec. 3.2 "Expert replacement policy", Fig. 7 steps 3-4:
+ * the experts activated most during this verification pass become the draft experts of the
+ * next speculation phase).  counts[e] = expert_offsets[e+1] - expert_offsets[e];
+ *   hot_ids[0..n_hot-1] = the n_hot experts with the largest counts, ordered by descending
+ *   count, equal counts -> lower expert id first;  hot_counts[s] = counts[hot_ids[s]] (may be
+ *   NULL).  0 <= n_hot <= E. */
+int moe_hot_experts(const int32_t* expert_offsets, int E, int n_hot, int32_t* hot_ids,
+                    int32_t* hot_counts, void* stream);
 
 /* Helper for the multi-layer benchmark configuration (not part of the paper's method):
  * out[t] = x[t] / sqrt(mean_j x[t,j]^2 + eps) * gain, fp32 arithmetic, rounded to `dtype`. */

@@ -1,8 +1,8 @@
 """MI355X-native MoE verification layer (router top-k, permute, grouped SwiGLU, combine,
 greedy acceptance) as a C-ABI HIP library with a thin ctypes binding."""
 from .binding import (  # noqa: F401
-    SpecMoEError, lib_path, load_library, moe_combine, moe_expert_down, moe_expert_up_swiglu, moe_grouped_swiglu,
-    moe_grouped_swiglu_workspace_bytes, moe_permute, moe_rmsnorm, moe_route_topk, spec_accept,
+    SpecMoEError, lib_path, load_library, moe_combine, moe_expert_down, moe_expert_up_swiglu, moe_expert_up_swiglu_gather, moe_grouped_swiglu,
+    moe_grouped_swiglu_workspace_bytes, moe_hot_experts, moe_permute, moe_rmsnorm, moe_route_topk, spec_accept,
     status_string, EXPORTED_SYMBOLS,
 )
 from .layer import MoEVerifyLayer, MoEVerifyStack  # noqa: F401

@@ -17,7 +17,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "moe_route_topk", "moe_permute", "moe_grouped_swiglu_workspace_bytes", "moe_grouped_swiglu",
-    "moe_expert_up_swiglu", "moe_expert_down", "moe_combine", "spec_accept", "moe_rmsnorm", "specmoe_status_string", "specmoe_abi_version",
+    "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down", "moe_combine", "spec_accept", "moe_hot_experts", "moe_rmsnorm", "specmoe_status_string", "specmoe_abi_version",
 )
 
 F32, BF16 = 0, 1
@@ -53,15 +53,18 @@ def load_library(build_if_missing: bool = True):
     lib.moe_grouped_swiglu_workspace_bytes.restype = sz
     lib.moe_grouped_swiglu.argtypes = [vp, ip, vp, vp, vp, i, i, i, i, i, vp, vp, sz, vp]
     lib.moe_expert_up_swiglu.argtypes = [vp, ip, vp, vp, i, i, i, i, i, vp, vp]
+    lib.moe_expert_up_swiglu_gather.argtypes = [vp, ip, i, i, ip, vp, vp, i, i, i, i, i, vp, vp]
     lib.moe_expert_down.argtypes = [vp, ip, vp, i, i, i, i, i, vp, vp]
     lib.moe_combine.argtypes = [vp, ip, fp, vp, i, i, i, i, vp, vp]
     lib.spec_accept.argtypes = [ip, ip, i, i, ip, ip, vp]
+    lib.moe_hot_experts.argtypes = [ip, i, i, ip, ip, vp]
     lib.moe_rmsnorm.argtypes = [vp, vp, i, i, ctypes.c_float, i, vp, vp]
     lib.specmoe_status_string.argtypes = [i]
     lib.specmoe_status_string.restype = ctypes.c_char_p
     lib.specmoe_abi_version.restype = i
     for name in ("moe_route_topk", "moe_permute", "moe_grouped_swiglu", "moe_combine",
-                 "moe_expert_up_swiglu", "moe_expert_down",
+                 "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down",
+                 "moe_hot_experts",
                  "spec_accept", "moe_rmsnorm"):
         getattr(lib, name).restype = i
     _LIB = lib
@@ -151,6 +154,17 @@ def moe_expert_up_swiglu(x_perm, expert_offsets, w_gate, w_up, h, stream=None):
         _dtype_code(x_perm), _ptr(h, x_perm.dtype, "h"), _stream(stream)), "moe_expert_up_swiglu")
 
 
+def moe_expert_up_swiglu_gather(x, row_src, k, expert_offsets, w_gate, w_up, h, stream=None):
+    T, d = x.shape
+    n_rows = row_src.numel()
+    E, f, _ = w_gate.shape
+    _check(load_library().moe_expert_up_swiglu_gather(
+        _ptr(x, name="x"), _ptr(row_src, torch.int32, "row_src"), T, int(k),
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), _ptr(w_gate, x.dtype, "w_gate"),
+        _ptr(w_up, x.dtype, "w_up"), n_rows, d, f, E, _dtype_code(x), _ptr(h, x.dtype, "h"),
+        _stream(stream)), "moe_expert_up_swiglu_gather")
+
+
 def moe_expert_down(h, expert_offsets, w_down, y_perm, stream=None):
     n_rows, f = h.shape
     E, d, _ = w_down.shape
@@ -177,6 +191,14 @@ def spec_accept(draft_ids, target_ids, accept_len, out_tokens, stream=None):
         _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(target_ids, torch.int32, "target_ids"), B,
         gamma, _ptr(accept_len, torch.int32, "accept_len"),
         _ptr(out_tokens, torch.int32, "out_tokens"), _stream(stream)), "spec_accept")
+
+
+def moe_hot_experts(expert_offsets, hot_ids, hot_counts=None, stream=None):
+    E = expert_offsets.numel() - 1
+    _check(load_library().moe_hot_experts(
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), E, hot_ids.numel(),
+        _ptr(hot_ids, torch.int32, "hot_ids"), _ptr(hot_counts, torch.int32, "hot_counts"),
+        _stream(stream)), "moe_hot_experts")
 
 
 def moe_rmsnorm(x, gain, eps, out, stream=None):

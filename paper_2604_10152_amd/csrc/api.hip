@@ -74,6 +74,30 @@ int moe_expert_up_swiglu(const void* x_perm, const int32_t* expert_offsets, cons
                                      (const bf16_t*)w_up, n_rows, d_model, d_ff, E, (bf16_t*)h, s));
 }
 
+int moe_expert_up_swiglu_gather(const void* x, const int32_t* row_src, int T, int k,
+                                const int32_t* expert_offsets, const void* w_gate,
+                                const void* w_up, int n_rows, int d_model, int d_ff, int E,
+                                int dtype, void* h, void* stream) {
+    const int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
+    if (st != SPECMOE_OK) return st;
+    if (T < 0 || k < 1 || k > SPECMOE_MAX_TOPK || pairs_overflow(T, k) ||
+        (long long)n_rows > (long long)T * k)
+        return SPECMOE_ERR_SHAPE;
+    // the gathered loads address a token row through a 32-bit byte offset
+    if ((unsigned long long)T * (unsigned long long)d_model * esize(dtype) >= (1ull << 32))
+        return SPECMOE_ERR_SHAPE;
+    if (n_rows == 0) return SPECMOE_OK;
+    if (!x || !row_src || !expert_offsets || !w_gate || !w_up || !h) return SPECMOE_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (dtype == SPECMOE_F32)
+        return dev(launch_expert_up_f32((const float*)x, expert_offsets, (const float*)w_gate,
+                                        (const float*)w_up, n_rows, d_model, d_ff, E, (float*)h, s,
+                                        row_src, k));
+    return dev(launch_expert_up_bf16((const bf16_t*)x, expert_offsets, (const bf16_t*)w_gate,
+                                     (const bf16_t*)w_up, n_rows, d_model, d_ff, E, (bf16_t*)h, s,
+                                     row_src, k));
+}
+
 int moe_expert_down(const void* h, const int32_t* expert_offsets, const void* w_down, int n_rows,
                     int d_model, int d_ff, int E, int dtype, void* y_perm, void* stream) {
     const int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
@@ -129,6 +153,15 @@ int spec_accept(const int32_t* draft_ids, const int32_t* target_ids, int B, int 
                                   (hipStream_t)stream));
 }
 
+int moe_hot_experts(const int32_t* expert_offsets, int E, int n_hot, int32_t* hot_ids,
+                    int32_t* hot_counts, void* stream) {
+    if (E < 1 || E > SPECMOE_MAX_EXPERTS || n_hot < 0 || n_hot > E) return SPECMOE_ERR_SHAPE;
+    if (n_hot == 0) return SPECMOE_OK;
+    if (!expert_offsets || !hot_ids) return SPECMOE_ERR_NULL;
+    return dev(launch_hot_experts(expert_offsets, E, n_hot, hot_ids, hot_counts,
+                                  (hipStream_t)stream));
+}
+
 int moe_rmsnorm(const void* x, const void* gain, int T, int d_model, float eps, int dtype,
                 void* out, void* stream) {
     if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
@@ -150,6 +183,6 @@ const char* specmoe_status_string(int status) {
     }
 }
 
-int specmoe_abi_version(void) { return 1; }
+int specmoe_abi_version(void) { return 3; }
 
 }  // extern "C"

@@ -48,29 +48,32 @@ hipError_t launch_permute(const void* x, const int32_t* idx, int T, int d, int E
                           int32_t* row_of, hipStream_t s);
 hipError_t launch_expert_up_f32(const float* x_perm, const int32_t* offsets, const float* wg,
                                 const float* wu, int n_rows, int d, int f, int E, float* h,
-                                hipStream_t s);
+                                hipStream_t s, const int32_t* row_src = nullptr, int topk = 1);
 hipError_t launch_expert_down_f32(const float* h, const int32_t* offsets, const float* wd,
                                   int n_rows, int d, int f, int E, float* y, hipStream_t s);
 hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, const bf16_t* wg,
                                  const bf16_t* wu, int n_rows, int d, int f, int E, bf16_t* h,
-                                 hipStream_t s);
+                                 hipStream_t s, const int32_t* row_src = nullptr, int topk = 1);
 hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, const bf16_t* wd,
                                    int n_rows, int d, int f, int E, bf16_t* y, hipStream_t s);
 hipError_t launch_expert_up_bf16_large(const bf16_t* x_perm, const int32_t* offsets,
                                        const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
-                                       int f, int E, bf16_t* h, hipStream_t s);
+                                       int f, int E, bf16_t* h, hipStream_t s,
+    const int32_t* row_src, int topk);
 hipError_t launch_expert_down_bf16_large(const bf16_t* h, const int32_t* offsets,
                                          const bf16_t* wd, int n_rows, int d, int f, int E,
                                          bf16_t* y, hipStream_t s);
 hipError_t launch_expert_up_bf16_large16(const bf16_t* x_perm, const int32_t* offsets,
                                          const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
-                                         int f, int E, bf16_t* h, hipStream_t s);
+                                         int f, int E, bf16_t* h, hipStream_t s,
+    const int32_t* row_src, int topk);
 hipError_t launch_expert_down_bf16_large16(const bf16_t* h, const int32_t* offsets,
                                            const bf16_t* wd, int n_rows, int d, int f, int E,
                                            bf16_t* y, hipStream_t s);
 hipError_t launch_expert_up_bf16_small(const bf16_t* x_perm, const int32_t* offsets,
                                        const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
-                                       int f, int E, bf16_t* h, hipStream_t s);
+                                       int f, int E, bf16_t* h, hipStream_t s,
+    const int32_t* row_src, int topk);
 hipError_t launch_expert_down_bf16_small(const bf16_t* h, const int32_t* offsets,
                                          const bf16_t* wd, int n_rows, int d, int f, int E,
                                          bf16_t* y, hipStream_t s);
@@ -79,6 +82,8 @@ hipError_t launch_combine(const void* y_perm, const int32_t* row_of, const float
                           hipStream_t s);
 hipError_t launch_rmsnorm(const void* x, const void* gain, int T, int d, float eps, int dtype,
                           void* out, hipStream_t s);
+hipError_t launch_hot_experts(const int32_t* offsets, int E, int n, int32_t* hot_ids,
+                              int32_t* hot_counts, hipStream_t s);
 hipError_t launch_spec_accept(const int32_t* draft, const int32_t* target, int B, int gamma,
                               int32_t* accept_len, int32_t* out_tokens, hipStream_t s);
 

@@ -38,7 +38,8 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
     const int32_t* __restrict__ offsets, // [E+1]
     const bf16_t* __restrict__ W0,       // [E, N, K]   (gate, or down)
     const bf16_t* __restrict__ W1,       // [E, N, K]   (up; SWIGLU only)
-    int E, int N, int K, bf16_t* __restrict__ Cout /* [n_rows, N] */) {
+    int E, int N, int K, bf16_t* __restrict__ Cout /* [n_rows, N] */,
+    const int32_t* __restrict__ row_src /* nullable: A row r is A[row_src[r] / topk] */, int topk) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
 
     const int NT = (N + C::BN_OUT - 1) / C::BN_OUT;
@@ -59,7 +60,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_raw;
 
     // ---- global side of the wave-loads -------------------------------------------------
-    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(A + (size_t)row0 * K);
+    // with row_src the activation rows are gathered on the fly (A is then the token matrix)
+    const unsigned char* a_base =
+        reinterpret_cast<const unsigned char*>(A + (row_src ? (size_t)0 : (size_t)row0 * K));
     const size_t wrow = (size_t)t.expert * N + min(n0, N - 1);
     const unsigned char* w0 = reinterpret_cast<const unsigned char*>(W0 + wrow * K);
     const unsigned char* w1 = C::SWIGLU ? reinterpret_cast<const unsigned char*>(W1 + wrow * K)
@@ -73,7 +76,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
         for (int jj = 0; jj < C::A_PW; ++jj) {
             const int r = (wave + jj * C::NWAVES) * C::ROWS_PER_DMA + srow;
             const int c = pc ^ ((r / C::RPG) % C::CHUNKS);
-            a_off[jj] = (uint32_t)((min(r, tile_rows - 1) * K + c * 8) * 2);
+            const int rr = min(r, tile_rows - 1);
+            const unsigned arow = row_src ? (unsigned)(row_src[row0 + rr] / topk) : (unsigned)rr;
+            a_off[jj] = (arow * (unsigned)K + (unsigned)(c * 8)) * 2u;
             // this wave's A loads: wave-load j = wave + jj*NWAVES covers tile rows j*16.. ;
             // only loads that hold at least one real row are issued
             if ((wave + jj * C::NWAVES) * C::ROWS_PER_DMA < tile_rows) a_cnt = jj + 1;
@@ -318,7 +323,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
 template <typename C>
 hipError_t launch_pipe(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
                        const bf16_t* W1, int n_rows, int E, int N, int K, bf16_t* Cout,
-                       hipStream_t s) {
+                       hipStream_t s, const int32_t* row_src = nullptr, int topk = 1) {
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(
@@ -330,7 +335,7 @@ hipError_t launch_pipe(const bf16_t* A, const int32_t* offsets, const bf16_t* W0
     const long long NT = (N + C::BN_OUT - 1) / C::BN_OUT;
     const long long grid = grid_upper_bound(n_rows, E, C::BM, NT);
     hipLaunchKernelGGL(grouped_gemm_bf16_pipe_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS),
-                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout);
+                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout, row_src, topk);
     return hipGetLastError();
 }
 
@@ -338,9 +343,10 @@ hipError_t launch_pipe(const bf16_t* A, const int32_t* offsets, const bf16_t* W0
 
 hipError_t launch_expert_up_bf16_large(const bf16_t* x_perm, const int32_t* offsets,
                                        const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
-                                       int f, int E, bf16_t* h, hipStream_t s) {
+                                       int f, int E, bf16_t* h, hipStream_t s,
+                                       const int32_t* row_src, int topk) {
     return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, true>>(x_perm, offsets, wg, wu, n_rows, E, f,
-                                                             d, h, s);
+                                                             d, h, s, row_src, topk);
 }
 
 hipError_t launch_expert_down_bf16_large(const bf16_t* h, const int32_t* offsets,
@@ -355,9 +361,10 @@ hipError_t launch_expert_down_bf16_large(const bf16_t* h, const int32_t* offsets
 // lose ~10 % of HBM throughput) and a 4 / 6 stage ring (~70-120 KB of requests in flight per CU).
 hipError_t launch_expert_up_bf16_small(const bf16_t* x_perm, const int32_t* offsets,
                                        const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
-                                       int f, int E, bf16_t* h, hipStream_t s) {
+                                       int f, int E, bf16_t* h, hipStream_t s,
+                                       const int32_t* row_src, int topk) {
     return launch_pipe<PipeCfg<64, 128, 64, 4, 1, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f,
-                                                            d, h, s);
+                                                            d, h, s, row_src, topk);
 }
 
 hipError_t launch_expert_down_bf16_small(const bf16_t* h, const int32_t* offsets,

@@ -35,7 +35,8 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
     const int32_t* __restrict__ offsets, // [E+1]
     const bf16_t* __restrict__ W0,       // [E, N, K]   (gate, or down)
     const bf16_t* __restrict__ W1,       // [E, N, K]   (up; SWIGLU only)
-    int E, int N, int K, bf16_t* __restrict__ Cout /* [n_rows, N] */) {
+    int E, int N, int K, bf16_t* __restrict__ Cout /* [n_rows, N] */,
+    const int32_t* __restrict__ row_src /* nullable: A row r is A[row_src[r] / topk] */, int topk) {
     static_assert(C::BK == 32, "a stage is exactly one 16x16x32 k-step");
     constexpr int TM16 = C::BM / (16 * C::WM);       // 16-row A sub-tiles per wave
     constexpr int TN16 = C::BN / (16 * C::WN);       // 16-col B sub-tiles per wave
@@ -60,7 +61,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_raw;
 
     // ---- global side of the wave-loads (identical to the 32x32 kernel) --------------------
-    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(A + (size_t)row0 * K);
+    // with row_src the activation rows are gathered on the fly (A is then the token matrix)
+    const unsigned char* a_base =
+        reinterpret_cast<const unsigned char*>(A + (row_src ? (size_t)0 : (size_t)row0 * K));
     const size_t wrow = (size_t)t.expert * N + min(n0, N - 1);
     const unsigned char* w0 = reinterpret_cast<const unsigned char*>(W0 + wrow * K);
     const unsigned char* w1 = C::SWIGLU ? reinterpret_cast<const unsigned char*>(W1 + wrow * K)
@@ -74,7 +77,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
         for (int jj = 0; jj < C::A_PW; ++jj) {
             const int r = (wave + jj * C::NWAVES) * C::ROWS_PER_DMA + srow;
             const int c = pc ^ ((r / C::RPG) % C::CHUNKS);
-            a_off[jj] = (uint32_t)((min(r, tile_rows - 1) * K + c * 8) * 2);
+            const int rr = min(r, tile_rows - 1);
+            const unsigned arow = row_src ? (unsigned)(row_src[row0 + rr] / topk) : (unsigned)rr;
+            a_off[jj] = (arow * (unsigned)K + (unsigned)(c * 8)) * 2u;
             if ((wave + jj * C::NWAVES) * C::ROWS_PER_DMA < tile_rows) a_cnt = jj + 1;
         }
 #pragma unroll
@@ -268,7 +273,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
 template <typename C>
 hipError_t launch_pipe16(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
                          const bf16_t* W1, int n_rows, int E, int N, int K, bf16_t* Cout,
-                         hipStream_t s) {
+                         hipStream_t s, const int32_t* row_src = nullptr, int topk = 1) {
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(
@@ -280,7 +285,7 @@ hipError_t launch_pipe16(const bf16_t* A, const int32_t* offsets, const bf16_t* 
     const long long NT = (N + C::BN_OUT - 1) / C::BN_OUT;
     const long long grid = grid_upper_bound(n_rows, E, C::BM, NT);
     hipLaunchKernelGGL(grouped_gemm_bf16_pipe16_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS),
-                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout);
+                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout, row_src, topk);
     return hipGetLastError();
 }
 
@@ -288,9 +293,10 @@ hipError_t launch_pipe16(const bf16_t* A, const int32_t* offsets, const bf16_t* 
 
 hipError_t launch_expert_up_bf16_large16(const bf16_t* x_perm, const int32_t* offsets,
                                          const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
-                                         int f, int E, bf16_t* h, hipStream_t s) {
+                                         int f, int E, bf16_t* h, hipStream_t s,
+                                         const int32_t* row_src, int topk) {
     return launch_pipe16<PipeCfg<320, 256, 32, 4, 2, 4, true>>(x_perm, offsets, wg, wu, n_rows, E,
-                                                               f, d, h, s);
+                                                               f, d, h, s, row_src, topk);
 }
 
 hipError_t launch_expert_down_bf16_large16(const bf16_t* h, const int32_t* offsets,

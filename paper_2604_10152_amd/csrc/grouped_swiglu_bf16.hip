@@ -61,7 +61,8 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_kernel(
     const int32_t* __restrict__ offsets, // [E+1]
     const bf16_t* __restrict__ W0,       // [E, N, K]   (gate, or down)
     const bf16_t* __restrict__ W1,       // [E, N, K]   (up; SWIGLU only)
-    int E, int N, int K, bf16_t* __restrict__ Cout /* [n_rows, N] */) {
+    int E, int N, int K, bf16_t* __restrict__ Cout /* [n_rows, N] */,
+    const int32_t* __restrict__ row_src /* nullable: A row r is A[row_src[r] / topk] */, int topk) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds_a = reinterpret_cast<bf16_t*>(lds_raw);                 // [2][BM*BK]
     bf16_t* lds_b = lds_a + 2 * C::BM * kBK;                            // [2][BN*BK]
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_kernel(
     //      clamped into the valid range so every load stays in bounds) ---------------------
     constexpr int kRowsPerPass = C::THREADS / kChunksPerRow;    // tile rows one load pass covers
     static_assert(!C::SWIGLU || (C::BN / 2) % kRowsPerPass == 0, "gate/up split must align");
-    const bf16_t* a_base = A + (size_t)row0 * K;
+    const bf16_t* a_base = A + (row_src ? (size_t)0 : (size_t)row0 * K);
     const bf16_t* w0 = W0 + ((size_t)expert * N + min(n0, N - 1)) * K;
     const bf16_t* w1 = C::SWIGLU ? W1 + ((size_t)expert * N + min(n0, N - 1)) * K : nullptr;
     const int n_left = N - n0;                             // weight rows left from n0 (>= 1)
@@ -113,7 +114,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_kernel(
 #pragma unroll
         for (int l = 0; l < C::A_LD; ++l) {
             const int r = r0 + l * kRowsPerPass;
-            a_off[l] = (uint32_t)(min(r, tile_rows - 1) * K + c * 8);
+            const int rr = min(r, tile_rows - 1);
+            const unsigned arow = row_src ? (unsigned)(row_src[row0 + rr] / topk) : (unsigned)rr;
+            a_off[l] = arow * (unsigned)K + (unsigned)(c * 8);
             a_lds[l] = lds_off(r, c);
         }
 #pragma unroll
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_kernel(
 template <typename C>
 hipError_t launch_one(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
                       const bf16_t* W1, int n_rows, int E, int N, int K, bf16_t* Cout,
-                      hipStream_t s) {
+                      hipStream_t s, const int32_t* row_src = nullptr, int topk = 1) {
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(
@@ -283,7 +286,7 @@ hipError_t launch_one(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
     long long grid = max_mt * NT;
     grid = (grid + kXcds - 1) / kXcds * kXcds;
     hipLaunchKernelGGL(grouped_gemm_bf16_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS),
-                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout);
+                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout, row_src, topk);
     return hipGetLastError();
 }
 
@@ -313,13 +316,13 @@ static inline bool use_regstaged() {
 // own stream.
 hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, const bf16_t* wg,
                                  const bf16_t* wu, int n_rows, int d, int f, int E, bf16_t* h,
-                                 hipStream_t s) {
+                                 hipStream_t s, const int32_t* row_src, int topk) {
     if (n_rows == 0) return hipSuccess;
     if (large_batch(n_rows, E))
-        return use_mfma32() ? launch_expert_up_bf16_large(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s)
-                            : launch_expert_up_bf16_large16(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s);
-    if (!use_regstaged() && d >= kLongK) return launch_expert_up_bf16_small(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s);
-    return launch_one<TileCfg<64, 128, 1, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s);
+        return use_mfma32() ? launch_expert_up_bf16_large(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk)
+                            : launch_expert_up_bf16_large16(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk);
+    if (!use_regstaged() && d >= kLongK) return launch_expert_up_bf16_small(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk);
+    return launch_one<TileCfg<64, 128, 1, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s, row_src, topk);
 }
 
 hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, const bf16_t* wd,

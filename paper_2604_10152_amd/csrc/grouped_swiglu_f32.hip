@@ -32,7 +32,7 @@ template <bool kSwiglu>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_f32_kernel(
     const float* __restrict__ A, const int32_t* __restrict__ offsets,
     const float* __restrict__ W0, const float* __restrict__ W1, int E, int N, int K,
-    float* __restrict__ C) {
+    float* __restrict__ C, const int32_t* __restrict__ row_src, int topk) {
     __shared__ float As[kBK][kBM + 4];
     __shared__ float B0s[kBK][kBN + 4];
     __shared__ float B1s[kSwiglu ? kBK : 1][kBN + 4];
@@ -50,7 +50,9 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_f32_kernel(
             const int flat = tid + i * kThreads;       // 64 rows x 16 k
             const int r = flat / kBK, kk = flat % kBK;
             const int gr = row0 + r, gk = k0 + kk, gn = n0 + r;
-            As[kk][r] = (gr < row_end && gk < K) ? A[(size_t)gr * K + gk] : 0.f;
+            // with row_src the activation rows are gathered from the token matrix on the fly
+            const size_t ar = (row_src && gr < row_end) ? (size_t)(row_src[gr] / topk) : (size_t)gr;
+            As[kk][r] = (gr < row_end && gk < K) ? A[ar * K + gk] : 0.f;
             B0s[kk][r] = (gn < N && gk < K) ? w0[(size_t)gn * K + gk] : 0.f;
             if (kSwiglu) B1s[kk][r] = (gn < N && gk < K) ? w1[(size_t)gn * K + gk] : 0.f;
         }
@@ -96,11 +98,11 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_f32_kernel(
 
 hipError_t launch_expert_up_f32(const float* x_perm, const int32_t* offsets, const float* wg,
                                 const float* wu, int n_rows, int d, int f, int E, float* h,
-                                hipStream_t s) {
+                                hipStream_t s, const int32_t* row_src, int topk) {
     if (n_rows == 0) return hipSuccess;
     const int max_mt = n_rows / kBM + E;           // sum_e ceil(M_e/BM) <= floor(P/BM) + E
     hipLaunchKernelGGL(grouped_gemm_f32_kernel<true>, dim3((f + kBN - 1) / kBN, max_mt),
-                       dim3(kThreads), 0, s, x_perm, offsets, wg, wu, E, f, d, h);
+                       dim3(kThreads), 0, s, x_perm, offsets, wg, wu, E, f, d, h, row_src, topk);
     return hipGetLastError();
 }
 
@@ -109,7 +111,8 @@ hipError_t launch_expert_down_f32(const float* h, const int32_t* offsets, const 
     if (n_rows == 0) return hipSuccess;
     const int max_mt = n_rows / kBM + E;
     hipLaunchKernelGGL(grouped_gemm_f32_kernel<false>, dim3((d + kBN - 1) / kBN, max_mt),
-                       dim3(kThreads), 0, s, h, offsets, wd, (const float*)nullptr, E, d, f, y);
+                       dim3(kThreads), 0, s, h, offsets, wd, (const float*)nullptr, E, d, f, y,
+                       (const int32_t*)nullptr, 1);
     return hipGetLastError();
 }
 

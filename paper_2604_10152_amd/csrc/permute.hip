@@ -18,6 +18,10 @@ constexpr int kPermWaves = 8;
 constexpr int kPermThreads = kPermWaves * kWave;
 constexpr int kBatch = 8;          // index rows fetched ahead per wavefront
 
+// SMALL_E (E <= 64): in phase (C) lane e keeps expert e's cursor in a register and the loop
+// over the distinct experts of a 64-pair row uses readlane instead of an LDS read-modify-write
+// chain (the chain dominated the kernel: 19 -> ~9 us at 4096 pairs).
+template <bool SMALL_E>
 __global__ __launch_bounds__(kPermThreads) void permute_index_kernel(
     const int32_t* __restrict__ idx, int P, int E, int32_t* __restrict__ offsets,
     int32_t* __restrict__ row_src, int32_t* __restrict__ row_of) {
@@ -85,6 +89,7 @@ __global__ __launch_bounds__(kPermThreads) void permute_index_kernel(
     __syncthreads();
 
     const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
+    int cursor = (SMALL_E && lane < E) ? mine[lane] : 0;                // lane e: cursor of expert e
     for (int base0 = lo; base0 < hi; base0 += kWave * kBatch) {         // (C)
         int ev[kBatch];
 #pragma unroll
@@ -101,12 +106,18 @@ __global__ __launch_bounds__(kPermThreads) void permute_index_kernel(
             int dest = 0;
             while (todo) {
                 const int leader = __ffsll((long long)todo) - 1;
-                const int cur = __shfl(e, leader, kWave);
+                const int cur = __builtin_amdgcn_readlane(e, leader);
                 const unsigned long long grp = __ballot(e == cur);
-                if (e == cur) dest = mine[cur] + __popcll(grp & lt_mask);
-                __builtin_amdgcn_wave_barrier();
-                if (lane == leader) mine[cur] += __popcll(grp);
-                __builtin_amdgcn_wave_barrier();
+                if (SMALL_E) {
+                    const int first = __builtin_amdgcn_readlane(cursor, cur);
+                    if (e == cur) dest = first + __popcll(grp & lt_mask);
+                    if (lane == cur) cursor += __popcll(grp);
+                } else {
+                    if (e == cur) dest = mine[cur] + __popcll(grp & lt_mask);
+                    __builtin_amdgcn_wave_barrier();
+                    if (lane == leader) mine[cur] += __popcll(grp);
+                    __builtin_amdgcn_wave_barrier();
+                }
                 todo &= ~grp;
             }
             if (valid) { row_src[dest] = p; row_of[p] = dest; }
@@ -138,8 +149,12 @@ hipError_t launch_permute(const void* x, const int32_t* idx, int T, int d, int E
                           int32_t* row_of, hipStream_t s) {
     const int P = T * k;
     size_t lds = (size_t)(kPermWaves + 1) * E * sizeof(int);
-    hipLaunchKernelGGL(permute_index_kernel, dim3(1), dim3(kPermThreads), lds, s, idx, P, E,
-                       offsets, row_src, row_of);
+    if (E <= kWave)
+        hipLaunchKernelGGL(permute_index_kernel<true>, dim3(1), dim3(kPermThreads), lds, s, idx, P,
+                           E, offsets, row_src, row_of);
+    else
+        hipLaunchKernelGGL(permute_index_kernel<false>, dim3(1), dim3(kPermThreads), lds, s, idx,
+                           P, E, offsets, row_src, row_of);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || x_perm == nullptr || P == 0) return err;
     const size_t row_bytes = (size_t)d * (dtype == 0 ? 4 : 2);

@@ -13,9 +13,13 @@ class MoEVerifyLayer:
     T tokens = B sequences x (gamma+1) positions (the tokens one verification pass scores).
     """
 
-    def __init__(self, T, d_model, d_ff, E, k, dtype, device="cuda", renorm=True):
+    def __init__(self, T, d_model, d_ff, E, k, dtype, device="cuda", renorm=True,
+                 fuse_gather=True):
+        """fuse_gather: moe_permute writes indices only and the gate/up GEMM gathers token rows
+        itself (moe_expert_up_swiglu_gather); False materialises x_perm first."""
         self.T, self.d, self.f, self.E, self.k = T, d_model, d_ff, E, k
         self.dtype, self.renorm = dtype, renorm
+        self.fuse_gather = fuse_gather and T * d_model * (4 if dtype == torch.float32 else 2) < 2 ** 32
         P = T * k
         dev = torch.device(device)
         i32 = dict(dtype=torch.int32, device=dev)
@@ -35,11 +39,15 @@ class MoEVerifyLayer:
         recorded around the gate/up expert GEMM (used by the benchmark's roofline figure)."""
         out = self.out if out is None else out
         B.moe_route_topk(x, w_router, bias, self.k, self.renorm, self.topk_idx, self.topk_w, stream)
-        B.moe_permute(x, self.topk_idx, self.E, self.x_perm, self.expert_offsets, self.row_src,
-                      self.row_of, stream)
+        B.moe_permute(x, self.topk_idx, self.E, None if self.fuse_gather else self.x_perm,
+                      self.expert_offsets, self.row_src, self.row_of, stream)
         if up_events is not None:
             up_events[0].record(stream)
-        B.moe_expert_up_swiglu(self.x_perm, self.expert_offsets, w_gate, w_up, self.h, stream)
+        if self.fuse_gather:
+            B.moe_expert_up_swiglu_gather(x, self.row_src, self.k, self.expert_offsets, w_gate,
+                                          w_up, self.h, stream)
+        else:
+            B.moe_expert_up_swiglu(self.x_perm, self.expert_offsets, w_gate, w_up, self.h, stream)
         if up_events is not None:
             up_events[1].record(stream)
         B.moe_expert_down(self.h, self.expert_offsets, w_down, self.y_perm, stream)

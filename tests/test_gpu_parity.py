@@ -187,6 +187,26 @@ def test_permute_degenerate():
     assert off.tolist() == [0, 1, 3, 4, 4] and rs.tolist() == [1, 0, 2, 3] and xp is None
 
 
+def test_hot_experts_match_oracle():
+    """Sec. 3.2 replacement policy input: the N most activated experts, ties to the lower id."""
+    _say("hot experts")
+    cases = [np.array([3, 9, 9, 1, 9, 0, 9, 2]), np.array([5] * 130), np.arange(70)[::-1] % 7,
+             np.array([0, 0, 0, 4])]
+    rng = np.random.default_rng(3)
+    cases.append(rng.integers(0, 50, size=1024))
+    for counts in cases:
+        E = len(counts)
+        off = torch.from_numpy(np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)).cuda()
+        for n in sorted({1, min(4, E), E}):
+            ids = torch.full((n,), -1, dtype=I32, device="cuda")
+            cnt = torch.full((n,), -1, dtype=I32, device="cuda")
+            sm.moe_hot_experts(off, ids, cnt)
+            torch.cuda.synchronize()
+            want = orc.hot_experts(counts, n)
+            assert (ids.cpu().numpy() == want).all()
+            assert (cnt.cpu().numpy() == counts[want]).all()
+
+
 # ------------------------------------------------------------------ a3 experts
 def _gpu_grouped(xp, off, wg, wu, wd):
     n, d = xp.shape
@@ -355,6 +375,33 @@ def test_layer_sampled_tokens(cfg_id, n_sample):
     print(f"   cfg{cfg_id}: sampled-row err={err:.3e}", flush=True)
     assert err <= TOL[cfg.torch_dtype]
     assert torch.isfinite(out.float()).all()
+
+
+@pytest.mark.parametrize("name,cfg", [
+    ("cfg1-f32", synth.CONFIGS[1]),
+    ("bf16-few-rows-short-k", synth.MoEConfig("g1", "bf16", 256, 384, 8, 2, 10, 3, 1 / 16, 0.05, 1.0)),
+    ("bf16-few-rows-long-k", synth.MoEConfig("g2", "bf16", 4096, 256, 4, 2, 10, 3, 1 / 64, 0.05, 1.0)),
+    ("bf16-large-batch", synth.MoEConfig("g3", "bf16", 256, 384, 4, 2, 150, 3, 1 / 16, 0.05, 1.0)),
+])
+def test_gather_fused_equals_materialised(name, cfg):
+    """moe_expert_up_swiglu_gather(x, row_src) must equal moe_permute(x -> x_perm) followed by
+    moe_expert_up_swiglu(x_perm) bit for bit (same kernel, only the row addresses differ); the
+    materialised path is itself checked against the oracle above."""
+    _say(f"gather fused vs materialised {name}")
+    L = synth.make_layer(cfg, "cuda", seed=21)
+    outs = []
+    for fuse in (True, False):
+        layer = sm.MoEVerifyLayer(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
+                                  renorm=cfg.renorm, fuse_gather=fuse)
+        assert layer.fuse_gather == fuse
+        out = layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"])
+        torch.cuda.synchronize()
+        outs.append((out.clone(), layer.h.clone()))
+    assert torch.equal(outs[0][1], outs[1][1])
+    assert torch.equal(outs[0][0], outs[1][0])
+    want = orc.moe_layer_brute_force(f64(L["x"]), f64(L["w_router"]), LazyF64(L["w_gate"]),
+                                     LazyF64(L["w_up"]), LazyF64(L["w_down"]), cfg.k)
+    assert row_rel_err(f64(outs[0][0]), want) <= TOL[cfg.torch_dtype]
 
 
 def test_identical_experts_invariant_on_gpu():

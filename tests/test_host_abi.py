@@ -29,7 +29,7 @@ def test_header_and_library_agree(lib):
     assert set(declared) == set(binding.EXPORTED_SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.specmoe_abi_version() == 1
+    assert lib.specmoe_abi_version() == 3
 
 
 def test_status_strings(lib):
@@ -88,6 +88,17 @@ def test_grouped_validation(lib):
     assert f(N, N, N, N, N, 0, 64, 64, 2, 1, N, N, 0, N) == 0     # no rows: nothing to do
 
 
+def test_gather_up_validation(lib):
+    f = lib.moe_expert_up_swiglu_gather
+    assert f(P, P, 4, 2, P, P, P, 8, 64, 64, 2, 7, P, N) == 3
+    assert f(P, P, 4, 2, P, P, P, 9, 64, 64, 2, 1, P, N) == 2            # n_rows > T*k
+    assert f(P, P, 4, 0, P, P, P, 8, 64, 64, 2, 1, P, N) == 2            # k < 1
+    assert f(P, P, 2 ** 20, 2, P, P, P, 8, 4096, 64, 2, 1, P, N) == 2    # 32-bit row offsets
+    assert f(N, P, 4, 2, P, P, P, 8, 64, 64, 2, 1, P, N) == 1
+    assert f(P, N, 4, 2, P, P, P, 8, 64, 64, 2, 1, P, N) == 1
+    assert f(N, N, 4, 2, N, N, N, 0, 64, 64, 2, 1, N, N) == 0
+
+
 def test_combine_accept_rmsnorm_validation(lib):
     c = lib.moe_combine
     assert c(P, P, P, N, 4, 8, 2, 3, P, N) == 3
@@ -100,6 +111,12 @@ def test_combine_accept_rmsnorm_validation(lib):
     assert a(N, P, 4, 3, P, P, N) == 1
     assert a(P, P, 4, 3, N, P, N) == 1
     assert a(N, N, 0, 3, N, N, N) == 0
+    h = lib.moe_hot_experts
+    assert h(P, 0, 0, P, N, N) == 2
+    assert h(P, 8, 9, P, N, N) == 2
+    assert h(N, 8, 2, P, N, N) == 1
+    assert h(P, 8, 2, N, N, N) == 1
+    assert h(N, 8, 0, N, N, N) == 0
     r = lib.moe_rmsnorm
     assert r(P, P, 4, 8, 1e-5, 2, P, N) == 3
     assert r(P, P, 4, 8, -1.0, 0, P, N) == 2
