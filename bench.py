@@ -2,10 +2,10 @@
 """Benchmark of the MoE verify layer on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic input that is already
-resident in HBM: moe_route_topk -> moe_permute -> moe_expert_up_swiglu -> moe_expert_down ->
+resident in HBM: moe_route_topk -> moe_permute -> moe_expert_up_swiglu_gather -> moe_expert_down ->
 moe_combine -> spec_accept.  Prints ONE JSON line (see README / design notes for the fields).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..4] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
 """
 import argparse
 import json
@@ -139,7 +139,9 @@ def main():
 
     # dominant kernel: the gate/up expert GEMM with the SwiGLU epilogue (2/3 of the flops)
     up_flops = 4.0 * P * d * f
-    up_bytes = (active * 2 * d * f + P * d + P * f) * esize
+    # bytes: the active experts' two matrices once, every x row once (the gather re-reads hit
+    # the cache), h once
+    up_bytes = (active * 2 * d * f + cfg.T * d + P * f) * esize
     if cfg.dtype == "bf16" and args.config == 4:
         roof = {"bound": "mfma", "achieved": up_flops / (up_ms * 1e-3) / 1e12,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
@@ -153,7 +155,9 @@ def main():
     if cfg.dtype != "bf16":
         roof["kernel"] = "grouped_gemm_f32_kernel<true> (gate/up + SwiGLU)"
     elif args.config == 4:
-        roof["kernel"] = "grouped_gemm_bf16_pipe_kernel<PipeCfg<320,256,32,4,2,4,true>> (gate/up + SwiGLU)"
+        roof["kernel"] = "grouped_gemm_bf16_pipe16_kernel<PipeCfg<320,256,32,4,2,4,true>> (gate/up + SwiGLU)"
+    elif d >= 4096:
+        roof["kernel"] = "grouped_gemm_bf16_pipe_kernel<PipeCfg<64,128,64,4,1,2,true>> (gate/up + SwiGLU)"
     else:
         roof["kernel"] = "grouped_gemm_bf16_kernel<TileCfg<64,128,1,2,true>> (gate/up + SwiGLU)"
     roof["kernel_ms"] = up_ms
