@@ -61,12 +61,12 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
 
     // ---- global side of the wave-loads -------------------------------------------------
     // with row_src the activation rows are gathered on the fly (A is then the token matrix)
-    const unsigned char* a_base =
-        reinterpret_cast<const unsigned char*>(A + (row_src ? (size_t)0 : (size_t)row0 * K));
+    const unsigned char* a_base = uniform_ptr(
+        reinterpret_cast<const unsigned char*>(A + (row_src ? (size_t)0 : (size_t)row0 * K)));
     const size_t wrow = (size_t)t.expert * N + min(n0, N - 1);
-    const unsigned char* w0 = reinterpret_cast<const unsigned char*>(W0 + wrow * K);
-    const unsigned char* w1 = C::SWIGLU ? reinterpret_cast<const unsigned char*>(W1 + wrow * K)
-                                        : nullptr;
+    const unsigned char* w0 = uniform_ptr(reinterpret_cast<const unsigned char*>(W0 + wrow * K));
+    const unsigned char* w1 =
+        C::SWIGLU ? uniform_ptr(reinterpret_cast<const unsigned char*>(W1 + wrow * K)) : nullptr;
     const int n_left = N - n0;
     uint32_t a_off[C::A_PW], b_off[C::B_PW];
     int a_cnt = 0;                               // A wave-loads this wave issues per stage

@@ -64,33 +64,61 @@ __device__ __forceinline__ EvenSplit even_split(int M) {
     return s;
 }
 
-// GRAN = row granule of the matrix instruction in use (32 or 16)
+// GRAN = row granule of the matrix instruction in use (32 or 16).
+// Wave-parallel: lane e works out expert e's split (64 experts per sweep), the running tile
+// count comes from a wave scan, and the owning expert is the first lane whose range reaches the
+// tile index.  Every wave of the workgroup calls this with all 64 lanes active and gets the same
+// answer; a scalar walk over the experts costs several microseconds of integer divisions per
+// workgroup, this one memory round trip and ~100 vector instructions.
 template <int BM_MAX, int GRAN = 32>
 __device__ __forceinline__ bool locate_tile_even(const int32_t* __restrict__ offsets, int E,
                                                  int NT, unsigned block_id, TileLoc& t) {
+    const int lane = threadIdx.x % kWave;
     int total_mt = 0;
-    for (int e = 0; e < E; ++e) total_mt += even_split<BM_MAX, GRAN>(offsets[e + 1] - offsets[e]).mt;
+    for (int e0 = 0; e0 < E; e0 += kWave) {
+        const int e = e0 + lane;
+        const int M = e < E ? offsets[e + 1] - offsets[e] : 0;
+        total_mt += wave_sum(even_split<BM_MAX, GRAN>(M).mt);
+    }
     const long long G = (long long)total_mt * NT;
     const long long per_xcd = (G + kXcds - 1) / kXcds;
     const long long slot = block_id / kXcds;
     const long long L = (long long)(block_id % kXcds) * per_xcd + slot;
     if (slot >= per_xcd || L >= G) return false;
-    long long base = 0;
-    for (int e = 0; e < E; ++e) {
-        const int lo = offsets[e], hi = offsets[e + 1];
+    int base_mt = 0;                              // m-tiles of the experts before this sweep
+    int expert = -1, row0 = 0, rows = 0, nt = 0;
+    for (int e0 = 0; e0 < E && expert < 0; e0 += kWave) {
+        const int e = e0 + lane;
+        const int lo = e < E ? offsets[e] : 0, hi = e < E ? offsets[e + 1] : 0;
         const EvenSplit sp = even_split<BM_MAX, GRAN>(hi - lo);
-        if (L < base + (long long)sp.mt * NT) {
-            const long long rem = L - base;
-            t.nt = (int)(rem / sp.mt);
-            const int mi = (int)(rem - (long long)t.nt * sp.mt);
-            t.expert = e;
-            t.row0 = lo + mi * sp.rpt;
-            t.tile_rows = min(sp.rpt, hi - t.row0);
-            return true;
+        int incl = sp.mt;                         // inclusive scan of mt over the lanes
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int v = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += v;
         }
-        base += (long long)sp.mt * NT;
+        const long long end = (long long)(base_mt + incl) * NT;      // tiles up to and incl. e
+        const unsigned long long hit = __ballot(sp.mt > 0 && L < end);
+        if (hit) {
+            const int src = __ffsll((long long)hit) - 1;              // first such expert
+            const int mt = __shfl(sp.mt, src, kWave), rpt = __shfl(sp.rpt, src, kWave);
+            const int excl = __shfl(incl, src, kWave) - mt;
+            const int lo_s = __shfl(lo, src, kWave), hi_s = __shfl(hi, src, kWave);
+            const long long rem = L - (long long)(base_mt + excl) * NT;
+            nt = (int)(rem / mt);
+            const int mi = (int)(rem - (long long)nt * mt);
+            expert = e0 + src;
+            row0 = lo_s + mi * rpt;
+            rows = min(rpt, hi_s - row0);
+        }
+        base_mt += __shfl(incl, kWave - 1, kWave);
     }
-    return false;
+    // the values are the same in every lane; say so to the compiler (scalar registers)
+    t.expert = __builtin_amdgcn_readfirstlane(expert);
+    t.row0 = __builtin_amdgcn_readfirstlane(row0);
+    t.tile_rows = __builtin_amdgcn_readfirstlane(rows);
+    t.nt = __builtin_amdgcn_readfirstlane(nt);
+    return t.expert >= 0;
 }
 
 // Upper bound of the grid (host side): sum_e ceil(M_e/BM) <= floor(n_rows/BM) + E.
