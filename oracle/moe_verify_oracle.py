@@ -37,7 +37,13 @@ exhaustive match patterns, softmax-over-selected closed form, k=E / k=1 / all-eq
 one-hot special cases, a stable library argsort, bincount, dense-MLP reduction for E=1,
 identical-experts invariant, token-permutation and expert-relabelling equivariance, and
 brute force per token against the step-wise (route, permute, grouped, combine) pipeline.
-No function in this file is unpinned.
+The speculation-phase functions (affinity table, nearest draft expert, draft routing), the
+sampling-based acceptance rule and the reporting helpers at the end of the file are pinned in
+the same test file: a library pairwise-distance routine, metric axioms and planted
+duplicates; reduction of the sampling rule to the greedy one on one-hot distributions, the
+"emitted token is distributed as the target" theorem and the sum-of-minima acceptance rate
+by Monte Carlo; numpy's first-occurrence argmax; the speed-up numbers the paper's own
+examples imply.  No function in this file is unpinned.
 """
 from __future__ import annotations
 
@@ -288,3 +294,139 @@ def hot_experts(counts, n):
     counts = np.asarray(counts)
     ranked = sorted(range(len(counts)), key=lambda e: (-int(counts[e]), e))
     return np.asarray(ranked[:n], dtype=np.int32)
+
+
+# --------------------------------------------------------------------------------------
+# n2  speculation phase: affinity table, nearest draft expert, draft routing   (Sec. 3.2)
+# --------------------------------------------------------------------------------------
+def affinity_table(w_gate, w_up, w_down):
+    """D[i,j] = L2 distance between the parameters of experts i and j (Sec. 3.2,
+    "Affinity-based expert selection mechanism": similarity of all expert pairs by L2
+    distance, computed once, offline).
+
+    Reading: an expert's parameters are its three matrices taken together, so
+    D[i,j]^2 = |Wg_i - Wg_j|_F^2 + |Wu_i - Wu_j|_F^2 + |Wd_i - Wd_j|_F^2.
+    """
+    E = len(w_gate)
+    D = np.zeros((E, E), dtype=F64)
+    for i in range(E):
+        for j in range(E):
+            sq = 0.0
+            for W in (w_gate, w_up, w_down):
+                diff = np.asarray(W[i], dtype=F64) - np.asarray(W[j], dtype=F64)
+                sq += float(np.sum(diff * diff))
+            D[i, j] = np.sqrt(sq)
+    return D
+
+
+def nearest_draft_expert(affinity, draft_ids):
+    """remap[e] = e if e is a draft expert, else the draft expert closest to e in the affinity
+    table (Fig. 8b); equal distances go to the lower expert id."""
+    affinity = np.asarray(affinity)
+    E = affinity.shape[0]
+    draft = [int(d) for d in draft_ids]
+    remap = np.zeros(E, dtype=np.int32)
+    for e in range(E):
+        if e in draft:
+            remap[e] = e
+        else:
+            remap[e] = min(draft, key=lambda dd: (affinity[e, dd], dd))
+    return remap
+
+
+def route_topk_draft(x, w_router, k, draft_ids, affinity, bias=None, renorm=True):
+    """Speculation-phase routing (Sec. 3.2): the target's gate is used as it is; a selected
+    expert that is not resident is replaced by its nearest draft expert.
+
+    Readings: the replacement is per slot and keeps the slot's gate weight; two slots of a
+    token may end up on the same draft expert (their weights then simply add in the mix).
+    """
+    idx, w, _ = route_topk(x, w_router, k, bias, renorm)
+    remap = nearest_draft_expert(affinity, draft_ids)
+    return remap[idx].astype(np.int32), w
+
+
+def moe_layer_draft(x, w_router, w_gate, w_up, w_down, k, draft_ids, affinity, bias=None,
+                    renorm=True):
+    """The MoE block as the draft model runs it: only draft experts compute (Sec. 3.2)."""
+    x = np.asarray(x, dtype=F64)
+    T, E = x.shape[0], len(w_gate)
+    idx, w = route_topk_draft(x, w_router, k, draft_ids, affinity, bias, renorm)
+    _, offsets, row_src, row_of = permute(idx, E)
+    y_perm = grouped_swiglu(gather_rows(x, row_src, k), offsets, w_gate, w_up, w_down)
+    return combine(y_perm, row_of, w, T, k), idx, w
+
+
+# --------------------------------------------------------------------------------------
+# n3  sampling-based verification   (Sec. 6.3: the rule of the speculative-sampling method
+#     the paper cites; temperature 1, so the probabilities are the models' softmax outputs)
+# --------------------------------------------------------------------------------------
+def _inverse_cdf(weights, u):
+    """Smallest id v with  sum_{v' <= v} weights[v'] > u * sum(weights)   (ids in order)."""
+    c = np.cumsum(np.asarray(weights, dtype=F64))
+    v = int(np.searchsorted(c, u * c[-1], side="right"))
+    return min(v, len(c) - 1)
+
+
+def accept_sample(draft, p_draft, p_target, u_accept, u_sample):
+    """Per sequence: draft token i (id x) is kept when u_accept[b,i] < min(1, pt(x)/pd(x)),
+    tested as u*pd(x) < pt(x); at the first rejection the token is redrawn from the
+    normalised positive part of (pt - pd) and everything after it is dropped; if all gamma
+    drafts are kept, one more token is drawn from the target's distribution at position
+    gamma.  Draws use the caller's uniforms u_sample[b] through the inverse CDF in id order.
+
+    draft [B,gamma] ids; p_draft [B,gamma,V]; p_target [B,gamma+1,V]; u_* in [0,1).
+    Returns accept_len [B] (kept drafts + 1) and out_tokens [B,gamma+1] padded with -1.
+    """
+    draft = np.asarray(draft)
+    p_draft = np.asarray(p_draft, dtype=F64)
+    p_target = np.asarray(p_target, dtype=F64)
+    B, gamma = draft.shape
+    accept_len = np.zeros(B, dtype=np.int32)
+    out = np.full((B, gamma + 1), -1, dtype=np.int32)
+    for b in range(B):
+        n = gamma
+        for i in range(gamma):
+            xid = int(draft[b, i])
+            if not (F64(u_accept[b, i]) * p_draft[b, i, xid] < p_target[b, i, xid]):
+                n = i
+                break
+        out[b, :n] = draft[b, :n]
+        if n < gamma:
+            resid = np.maximum(p_target[b, n] - p_draft[b, n], 0.0)
+            if resid.sum() <= 0.0:          # identical distributions cannot reject; guard only
+                resid = p_target[b, n]
+            out[b, n] = _inverse_cdf(resid, F64(u_sample[b]))
+        else:
+            out[b, n] = _inverse_cdf(p_target[b, gamma], F64(u_sample[b]))
+        accept_len[b] = n + 1
+    return accept_len, out
+
+
+# --------------------------------------------------------------------------------------
+# n4  reporting helpers
+# --------------------------------------------------------------------------------------
+def greedy_tokens(logits):
+    """Greedy decoding (Sec. 4 "SpecMoE configuration"): the id of the largest logit per row,
+    the lower id on ties."""
+    logits = np.asarray(logits)
+    out = np.zeros(logits.shape[0], dtype=np.int32)
+    for r in range(logits.shape[0]):
+        best = 0
+        for v in range(1, logits.shape[1]):
+            if logits[r, v] > logits[r, best]:
+                best = v
+        out[r] = best
+    return out
+
+
+def active_expert_bytes(counts, bytes_per_expert):
+    """Parameter bytes of the experts that at least one token activated: the volume an
+    offloading system would have to bring to the GPU for this block (Sec. 2.1 "Challenges",
+    Fig. 3b) and the volume this build reads from HBM."""
+    return int(np.count_nonzero(np.asarray(counts) > 0)) * int(bytes_per_expert)
+
+
+def expected_speedup(tau, gamma, c, lam=1.0):
+    """Eq. 1 (lam = 1) and Eq. 2:  S = tau / (gamma * c + lam)."""
+    return F64(tau) / (F64(gamma) * F64(c) + F64(lam))

@@ -361,3 +361,173 @@ def test_config3_router_is_skewed_like_the_paper_describes():
     s = orc.skewness(counts)
     assert 0.5 < s <= 1.0
     assert counts.sum() == cfg.P
+
+
+# ---------------------------------------------------------------- affinity / draft routing (n2)
+def test_affinity_matches_library_pairwise_distance():
+    """scipy's pairwise Euclidean distance on the experts' concatenated parameters."""
+    from scipy.spatial.distance import cdist
+    L = _tiny_layer(31, E=6)
+    D = orc.affinity_table(L["wg"], L["wu"], L["wd"])
+    flat = np.concatenate([L["wg"].reshape(6, -1), L["wu"].reshape(6, -1),
+                           L["wd"].reshape(6, -1)], axis=1)
+    np.testing.assert_allclose(D, cdist(flat, flat, metric="euclidean"), rtol=1e-12, atol=1e-12)
+
+
+def test_affinity_metric_axioms_and_planted_values():
+    L = _tiny_layer(32, E=5)
+    # expert 4 := expert 1 (distance 0), expert 3 := expert 0 + constant 0.5 in every entry
+    for k in ("wg", "wu", "wd"):
+        L[k][4] = L[k][1]
+        L[k][3] = L[k][0] + 0.5
+    D = orc.affinity_table(L["wg"], L["wu"], L["wd"])
+    n_param = L["wg"][0].size + L["wu"][0].size + L["wd"][0].size
+    assert np.all(np.diag(D) == 0) and np.allclose(D, D.T)
+    assert D[1, 4] == 0
+    assert D[0, 3] == pytest.approx(0.5 * np.sqrt(n_param), rel=1e-12)
+    for i, j, k in itertools.permutations(range(5), 3):
+        assert D[i, j] <= D[i, k] + D[k, j] + 1e-9
+
+
+def test_nearest_draft_expert_cases():
+    D = np.array([[0, 5, 1, 7],
+                  [5, 0, 3, 2],
+                  [1, 3, 0, 3],
+                  [7, 2, 3, 0]], dtype=np.float64)
+    assert orc.nearest_draft_expert(D, [0, 1, 2, 3]).tolist() == [0, 1, 2, 3]      # all resident
+    assert orc.nearest_draft_expert(D, [2]).tolist() == [2, 2, 2, 2]                # N = 1
+    assert orc.nearest_draft_expert(D, [3, 0]).tolist() == [0, 3, 0, 3]            # by distance
+    # expert 2 is equally far (3) from 1 and 3 -> lower id; order of draft_ids is irrelevant
+    assert orc.nearest_draft_expert(D, [3, 1]).tolist() == [1, 1, 1, 3]
+    assert orc.nearest_draft_expert(D, [1, 3]).tolist() == [1, 1, 1, 3]
+
+
+def test_route_draft_reductions():
+    L = _tiny_layer(33, T=40, E=6)
+    D = orc.affinity_table(L["wg"], L["wu"], L["wd"])
+    idx, w, _ = orc.route_topk(L["x"], L["wr"], 2)
+    idx_all, w_all = orc.route_topk_draft(L["x"], L["wr"], 2, list(range(6)), D)
+    assert np.array_equal(idx, idx_all) and np.array_equal(w, w_all)               # N = E
+    draft = [4, 1, 2]
+    idx_d, w_d = orc.route_topk_draft(L["x"], L["wr"], 2, draft, D)
+    assert set(np.unique(idx_d)) <= set(draft) and np.array_equal(w_d, w)
+    keep = np.isin(idx, draft)
+    assert np.array_equal(idx_d[keep], idx[keep])                                  # residents stay
+    for e_from, e_to in zip(idx[~keep], idx_d[~keep]):
+        assert all(D[e_from, e_to] <= D[e_from, dd] for dd in draft)
+
+
+def test_draft_layer_invariants():
+    """Copies of a resident expert are replaced by that expert without changing the output;
+    with every expert resident the draft layer is the target layer."""
+    L = _tiny_layer(34, T=12, E=6)
+    for k in ("wg", "wu", "wd"):
+        L[k][3] = L[k][0]
+        L[k][5] = L[k][2]
+    D = orc.affinity_table(L["wg"], L["wu"], L["wd"])
+    full = orc.moe_layer_stepwise(L["x"], L["wr"], L["wg"], L["wu"], L["wd"], 2)
+    out_all = orc.moe_layer_draft(L["x"], L["wr"], L["wg"], L["wu"], L["wd"], 2, range(6), D)[0]
+    np.testing.assert_allclose(out_all, full, rtol=1e-13, atol=1e-13)
+    out_d, idx_d, _ = orc.moe_layer_draft(L["x"], L["wr"], L["wg"], L["wu"], L["wd"], 2,
+                                          [0, 1, 2, 4], D)
+    assert set(np.unique(idx_d)) <= {0, 1, 2, 4}
+    np.testing.assert_allclose(out_d, full, rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------- sampling acceptance (n3)
+def _one_hot(ids, V):
+    p = np.zeros(ids.shape + (V,), dtype=np.float64)
+    np.put_along_axis(p, ids[..., None].astype(np.int64), 1.0, axis=-1)
+    return p
+
+
+def test_accept_sample_reduces_to_greedy_on_one_hot():
+    """Point-mass distributions: the rule keeps a draft iff it equals the target's token and
+    redraws exactly the target's token -> the greedy rule (pinned to Fig. 4 above)."""
+    r = _rng(41)
+    B, gamma, V = 64, 5, 11
+    draft = r.integers(0, V, size=(B, gamma)).astype(np.int32)
+    target = r.integers(0, V, size=(B, gamma + 1)).astype(np.int32)
+    agree = r.random(size=(B, gamma)) < 0.7
+    target[:, :gamma] = np.where(agree, draft, target[:, :gamma])
+    alen_g, out_g = orc.accept(draft, target)
+    alen_s, out_s = orc.accept_sample(draft, _one_hot(draft, V), _one_hot(target, V),
+                                      r.random(size=(B, gamma)), r.random(size=B))
+    assert np.array_equal(alen_g, alen_s) and np.array_equal(out_g, out_s)
+    g = _read_golden("fig4_accept.txt")
+    d1, t1 = np.array([g["draft"]]), np.array([g["target"]])
+    a1, o1 = orc.accept_sample(d1, _one_hot(d1, 40000), _one_hot(t1, 40000),
+                               np.full((1, 5), 0.5), np.array([0.5]))
+    assert a1[0] == g["generated"][0] and o1[0].tolist() == g["out_tokens"]
+
+
+def test_accept_sample_identical_distributions_keep_everything():
+    r = _rng(42)
+    B, gamma, V = 16, 4, 9
+    p = r.random(size=(B, gamma + 1, V)); p /= p.sum(-1, keepdims=True)
+    draft = r.integers(0, V, size=(B, gamma)).astype(np.int32)
+    alen, out = orc.accept_sample(draft, p[:, :gamma], p, r.random(size=(B, gamma)), r.random(size=B))
+    assert np.all(alen == gamma + 1) and np.array_equal(out[:, :gamma], draft)
+    assert np.all((out[:, gamma] >= 0) & (out[:, gamma] < V))
+
+
+def test_accept_sample_emits_the_target_distribution():
+    """The theorem behind the rule: with the draft token drawn from pd, the FIRST emitted
+    token is distributed exactly as pt, and the draft is kept with probability
+    sum_v min(pd, pt).  Monte Carlo over 2*10^5 sequences, V = 6."""
+    r = _rng(43)
+    V, B = 6, 200000
+    pd = np.array([0.05, 0.30, 0.10, 0.25, 0.20, 0.10])
+    pt = np.array([0.25, 0.05, 0.10, 0.15, 0.05, 0.40])
+    draft = r.choice(V, size=(B, 1), p=pd).astype(np.int32)
+    p_draft = np.broadcast_to(pd, (B, 1, V))
+    p_target = np.broadcast_to(pt, (B, 2, V))
+    alen, out = orc.accept_sample(draft, p_draft, p_target, r.random(size=(B, 1)), r.random(size=B))
+    freq = np.bincount(out[:, 0], minlength=V) / B
+    sigma = np.sqrt(pt * (1 - pt) / B)
+    assert np.all(np.abs(freq - pt) < 4.5 * sigma), (freq, pt)
+    keep = np.mean(alen == 2)
+    want = np.minimum(pd, pt).sum()
+    assert abs(keep - want) < 4.5 * np.sqrt(want * (1 - want) / B)
+    # after a kept draft the extra token follows pt as well
+    f2 = np.bincount(out[alen == 2, 1], minlength=V) / np.sum(alen == 2)
+    assert np.all(np.abs(f2 - pt) < 5 * np.sqrt(pt * (1 - pt) / np.sum(alen == 2)))
+
+
+def test_accept_sample_inverse_cdf_boundaries():
+    """Draws by hand: residual (pt - pd)+ = [0, .2, 0, .3] -> u < .4 gives id 1, else id 3."""
+    pd = np.array([[[0.5, 0.1, 0.4, 0.0]]])
+    pt = np.array([[[0.2, 0.3, 0.2, 0.3], [0.25, 0.25, 0.25, 0.25]]])
+    draft = np.array([[0]], dtype=np.int32)
+    # u*pd = u*0.5 < 0.2  <=> u < 0.4 keeps the draft
+    a, o = orc.accept_sample(draft, pd, pt, np.array([[0.39]]), np.array([0.6]))
+    assert a[0] == 2 and o[0].tolist() == [0, 2]          # kept; extra token: cdf .25 .5 .75 1
+    a, o = orc.accept_sample(draft, pd, pt, np.array([[0.41]]), np.array([0.39]))
+    assert a[0] == 1 and o[0].tolist() == [1, -1]
+    a, o = orc.accept_sample(draft, pd, pt, np.array([[0.41]]), np.array([0.40]))
+    assert a[0] == 1 and o[0].tolist() == [3, -1]
+    a, o = orc.accept_sample(draft, pd, pt, np.array([[0.99]]), np.array([0.0]))
+    assert o[0].tolist() == [1, -1]                        # zero-weight id 0 is never drawn
+
+
+# ---------------------------------------------------------------- reporting helpers (n4)
+def test_greedy_tokens_is_first_occurrence_argmax():
+    r = _rng(51)
+    logits = r.integers(-3, 4, size=(200, 17)).astype(np.float64)     # many exact ties
+    assert np.array_equal(orc.greedy_tokens(logits), np.argmax(logits, axis=1))
+    assert orc.greedy_tokens(np.array([[1.0, 5.0, 5.0, 2.0]])).tolist() == [1]
+
+
+def test_active_expert_bytes_and_speedup_model():
+    assert orc.active_expert_bytes([3, 0, 1, 0], 100) == 200
+    # Mixtral-shaped block: 3*d*f*2 bytes per expert; Table I lists 8 experts per block
+    assert orc.active_expert_bytes([1] * 8, 3 * 4096 * 14336 * 2) == 2818572288
+    # Eq. 1 is Eq. 2 at lambda = 1; a free draft model (c = 0) yields tau itself; with
+    # i.i.d. acceptance 0.7 and gamma = 4, tau = (1 - 0.7^5) / 0.3
+    tau = (1 - 0.7 ** 5) / 0.3
+    assert orc.expected_speedup(tau, 4, 0.0) == pytest.approx(2.7731, abs=1e-4)
+    assert orc.expected_speedup(tau, 4, 0.1, 1.0) == pytest.approx(tau / 1.4)
+    # Sec. 3.3's examples: gamma = 8 with lambda ~ 6 (B = 1) against lambda ~ 2 (B = 32):
+    # the larger batch triples-or-so the speed-up for a cheap draft model
+    s1, s32 = orc.expected_speedup(4.0, 8, 0.05, 6.0), orc.expected_speedup(4.0, 8, 0.05, 2.0)
+    assert s32 / s1 == pytest.approx(6.4 / 2.4)
