@@ -62,6 +62,74 @@ def cpu_baseline(cfg, L, draft, target, budget_s=15.0):
                       f"{cfg.E} experts' weights widened to fp64 beforehand (untimed); {t:.1f} s"}
 
 
+def speculation_bench(args):
+    """Timings of the speculation-phase / verification-rule kernels (one JSON line):
+    affinity table (offline), nearest draft expert, draft routing, sampling-based acceptance,
+    greedy head.  Each entry: microseconds per launch, algorithmic bytes, fraction of HBM peak."""
+    import torch
+    import paper_2604_10152_amd as sm
+    from workloads import synth
+    sm.load_library()
+    torch.cuda.set_device(0)
+    I32 = torch.int32
+    res = {}
+
+    def timed(name, fn, nbytes, reps=20):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        res[name] = {"us": us, "bytes": nbytes, "hbm_frac": nbytes / (us * 1e-6) / 1e9 / PEAK_HBM_GBS}
+
+    for cid in (2, 3):
+        cfg = synth.CONFIGS[cid]
+        L = synth.make_layer(cfg, "cuda", seed=args.seed)
+        E, d, f = cfg.E, cfg.d_model, cfg.d_ff
+        table = torch.empty((E, E), dtype=torch.float32, device="cuda")
+        ws = torch.empty((sm.moe_affinity_table_workspace_bytes(E),), dtype=torch.uint8, device="cuda")
+        timed(f"affinity_table_cfg{cid}",
+              lambda: sm.moe_affinity_table(L["w_gate"], L["w_up"], L["w_down"], table, ws),
+              3 * E * d * f * 2, reps=5)
+        layer = sm.MoEVerifyLayer(cfg.T, d, f, E, cfg.k, cfg.torch_dtype, renorm=cfg.renorm)
+        layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"])
+        n_draft = max(cfg.k, E // 4)
+        hot = torch.empty((n_draft,), dtype=I32, device="cuda")
+        remap = torch.empty((E,), dtype=I32, device="cuda")
+        timed(f"hot_experts+nearest_draft_cfg{cid}",
+              lambda: (sm.moe_hot_experts(layer.expert_offsets, hot),
+                       sm.moe_nearest_draft_expert(table, hot, remap)), E * E * 4)
+        T = cfg.B            # the draft model scores one token per sequence and step
+        dl = sm.MoEVerifyLayer(T, d, f, E, cfg.k, cfg.torch_dtype, renorm=cfg.renorm)
+        xs = L["x"][:T].contiguous()
+        timed(f"draft_layer_cfg{cid}_N{n_draft}_T{T}",
+              lambda: dl.forward(xs, L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
+                                 draft_remap=remap), 3 * n_draft * d * f * 2)
+        del L, layer, dl
+    B, gamma, V = 256, 7, 32000
+    g = torch.Generator(device="cuda").manual_seed(args.seed)
+    pt = torch.softmax(torch.randn(B, gamma + 1, V, generator=g, device="cuda") * 3, dim=-1)
+    pd = torch.softmax(torch.log(pt[:, :gamma]) + 0.7 * torch.randn(B, gamma, V, generator=g, device="cuda"), dim=-1)
+    draft = torch.multinomial(pd.reshape(-1, V), 1, generator=g).reshape(B, gamma).to(I32)
+    ua = torch.rand(B, gamma, generator=g, device="cuda")
+    us = torch.rand(B, generator=g, device="cuda")
+    alen = torch.empty((B,), dtype=I32, device="cuda")
+    out = torch.empty((B, gamma + 1), dtype=I32, device="cuda")
+    timed("spec_accept_sample_B256_g7_V32000",
+          lambda: sm.spec_accept_sample(draft, pd.contiguous(), pt, ua, us, alen, out), B * 2 * V * 4)
+    logits = torch.randn(B * (gamma + 1), V, generator=g, device="cuda").to(torch.bfloat16)
+    tok = torch.empty((B * (gamma + 1),), dtype=I32, device="cuda")
+    timed("spec_greedy_tokens_R2048_V32000_bf16", lambda: sm.spec_greedy_tokens(logits, tok),
+          B * (gamma + 1) * V * 2)
+    print(json.dumps({"metric": "speculation_phase_kernel_us", "data": "synthetic", "n_gpus": 1,
+                      "mean_accept_len_sampling": float(alen.float().mean().item()), "kernels": res}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +138,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--seed", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", choices=["verify", "speculation"], default="verify",
+                    help="verify (default): the MoE verify layer, the line the harness reads; "
+                         "speculation: per-kernel timings of the draft-routing / sampling rows")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one 1 GiB device copy (a kernel of known "
                          "traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE against)")
@@ -86,6 +157,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    if args.mode == "speculation":
+        speculation_bench(args)
+        return
     sm.load_library()
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]

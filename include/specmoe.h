@@ -47,6 +47,7 @@ typedef enum { SPECMOE_F32 = 0, SPECMOE_BF16 = 1 } specmoe_dtype;
 
 #define SPECMOE_MAX_EXPERTS 1024
 #define SPECMOE_MAX_TOPK 64
+#define SPECMOE_MAX_GAMMA 64     /* draft tokens per sequence in spec_accept_sample */
 
 /* Gate of one MoE block (Sec. 2.1: "the gate selects the top-K experts per token").
  *   logits l[t,e] = router_bias[e] + sum_j x[t,j] * w_router[e,j], accumulated in fp64;
@@ -134,6 +135,68 @@ int spec_accept(const int32_t* draft_ids, const int32_t* target_ids, int B, int 
  *   NULL).  0 <= n_hot <= E. */
 int moe_hot_experts(const int32_t* expert_offsets, int E, int n_hot, int32_t* hot_ids,
                     int32_t* hot_counts, void* stream);
+
+/* ---- speculation phase: draft experts and the affinity table (Sec. 3.2 "Affinity-based expert
+ * selection mechanism", Fig. 8) --------------------------------------------------------------
+ *
+ * moe_affinity_table: the offline table of pairwise L2 distances between the experts of one
+ * block.  An expert's parameters are its three matrices together:
+ *   affinity[i,j] = sqrt( |Wg_i-Wg_j|_F^2 + |Wu_i-Wu_j|_F^2 + |Wd_i-Wd_j|_F^2 ),  [E,E] float,
+ * exactly symmetric, zero diagonal.  w_gate, w_up [E,d_ff,d_model], w_down [E,d_model,d_ff] as
+ * for the expert entry points; d_model*d_ff*sizeof(element) must be a multiple of 16 and the
+ * weight pointers 16-byte aligned (else SPECMOE_ERR_SHAPE).  `workspace`: device scratch of at
+ * least moe_affinity_table_workspace_bytes(E) bytes, 8-byte aligned, contents irrelevant
+ * (SPECMOE_ERR_WORKSPACE if smaller).  Sums are accumulated in fp64 in a fixed order, so the
+ * result is deterministic. */
+size_t moe_affinity_table_workspace_bytes(int E);
+int moe_affinity_table(const void* w_gate, const void* w_up, const void* w_down, int E,
+                       int d_model, int d_ff, int dtype, float* affinity, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/* moe_nearest_draft_expert: for one set of draft (GPU-resident) experts, remap[e] = e if e is a
+ * draft expert, otherwise the draft expert d with the smallest affinity[e,d]; equal distances ->
+ * lower id.  draft_ids [n_draft] (device, any order, 1 <= n_draft <= E); ids outside [0,E) are
+ * ignored.  Typically draft_ids = hot_ids of moe_hot_experts. */
+int moe_nearest_draft_expert(const float* affinity, int E, const int32_t* draft_ids, int n_draft,
+                             int32_t* remap, void* stream);
+
+/* moe_route_topk_draft: the router of the draft model.  The target's gate is used unchanged
+ * (same logits, top-k and gate weights as moe_route_topk); every selected expert e is then
+ * replaced by remap[e] (device, [E]), slot by slot, keeping the slot's gate weight.  Two slots
+ * of a token may name the same draft expert; moe_permute / moe_combine handle that (the
+ * weights add).  All other arguments as moe_route_topk. */
+int moe_route_topk_draft(const void* x, const void* w_router, const float* router_bias, int T,
+                         int d_model, int E, int k, int renorm, int dtype, const int32_t* remap,
+                         int32_t* topk_idx, float* topk_w, void* stream);
+
+/* ---- sampling-based verification (Sec. 6.3: the models without pronounced hotness are verified
+ * with the sampling rule of the speculative-decoding method the paper cites, temperature 1) ----
+ * draft_ids [B,gamma]; p_draft [B,gamma,V] = the draft model's distribution at each drafted
+ * position; p_target [B,gamma+1,V]; u_accept [B,gamma] and u_sample [B]: uniforms in [0,1)
+ * supplied by the caller (the result is a deterministic function of the inputs).  All float.
+ * Draft i (id x) is kept iff u_accept[b,i]*p_draft[b,i,x] < p_target[b,i,x] (evaluated exactly,
+ * in fp64); n_b = number of drafts kept before the first rejection.  If n_b < gamma the token at
+ * position n_b is drawn from max(p_target - p_draft, 0) at that position, else from
+ * p_target[b,gamma]: the smallest id whose running sum (fp64, ascending ids) exceeds
+ * u_sample[b] * total.  accept_len[b] = n_b + 1; out_tokens[b,0..n_b-1] = the kept drafts,
+ * out_tokens[b,n_b] = the drawn token, remaining entries -1.  0 <= gamma <= SPECMOE_MAX_GAMMA.
+ * A draft id outside [0,V) is rejected. */
+int spec_accept_sample(const int32_t* draft_ids, const float* p_draft, const float* p_target,
+                       const float* u_accept, const float* u_sample, int B, int gamma, int V,
+                       int32_t* accept_len, int32_t* out_tokens, void* stream);
+
+/* Greedy head in front of spec_accept (Sec. 4 "SpecMoE configuration": greedy decoding):
+ * tokens[r] = id of the largest of logits[r,0..V-1] ([R,V], `dtype`), lower id on ties.
+ * Logits must not contain NaN. */
+int spec_greedy_tokens(const void* logits, int R, int V, int dtype, int32_t* tokens,
+                       void* stream);
+
+/* Parameter volume of the experts that at least one token activated in this pass (Sec. 2.1
+ * "Challenges in MoE model inference", Fig. 3(b): the bytes an offloading system migrates for
+ * the block; on this build: the weight bytes the expert kernels read from HBM).
+ * out_bytes[0] = #{e : expert_offsets[e+1] > expert_offsets[e]} * bytes_per_expert (device). */
+int moe_active_expert_bytes(const int32_t* expert_offsets, int E, long long bytes_per_expert,
+                            long long* out_bytes, void* stream);
 
 /* Helper for the multi-layer benchmark configuration (not part of the paper's method):
  * out[t] = x[t] / sqrt(mean_j x[t,j]^2 + eps) * gain, fp32 arithmetic, rounded to `dtype`. */

@@ -18,6 +18,8 @@ _LIB = None
 EXPORTED_SYMBOLS = (
     "moe_route_topk", "moe_permute", "moe_grouped_swiglu_workspace_bytes", "moe_grouped_swiglu",
     "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down", "moe_combine", "spec_accept", "moe_hot_experts", "moe_rmsnorm", "specmoe_status_string", "specmoe_abi_version",
+    "moe_affinity_table_workspace_bytes", "moe_affinity_table", "moe_nearest_draft_expert",
+    "moe_route_topk_draft", "spec_accept_sample", "spec_greedy_tokens", "moe_active_expert_bytes",
 )
 
 F32, BF16 = 0, 1
@@ -59,12 +61,22 @@ def load_library(build_if_missing: bool = True):
     lib.spec_accept.argtypes = [ip, ip, i, i, ip, ip, vp]
     lib.moe_hot_experts.argtypes = [ip, i, i, ip, ip, vp]
     lib.moe_rmsnorm.argtypes = [vp, vp, i, i, ctypes.c_float, i, vp, vp]
+    lib.moe_affinity_table_workspace_bytes.argtypes = [i]
+    lib.moe_affinity_table_workspace_bytes.restype = ctypes.c_size_t
+    lib.moe_affinity_table.argtypes = [vp, vp, vp, i, i, i, i, fp, vp, ctypes.c_size_t, vp]
+    lib.moe_nearest_draft_expert.argtypes = [fp, i, ip, i, ip, vp]
+    lib.moe_route_topk_draft.argtypes = [vp, vp, fp, i, i, i, i, i, i, ip, ip, fp, vp]
+    lib.spec_accept_sample.argtypes = [ip, fp, fp, fp, fp, i, i, i, ip, ip, vp]
+    lib.spec_greedy_tokens.argtypes = [vp, i, i, i, ip, vp]
+    lib.moe_active_expert_bytes.argtypes = [ip, i, ctypes.c_longlong, vp, vp]
     lib.specmoe_status_string.argtypes = [i]
     lib.specmoe_status_string.restype = ctypes.c_char_p
     lib.specmoe_abi_version.restype = i
     for name in ("moe_route_topk", "moe_permute", "moe_grouped_swiglu", "moe_combine",
                  "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down",
-                 "moe_hot_experts",
+                 "moe_hot_experts", "moe_affinity_table", "moe_nearest_draft_expert",
+                 "moe_route_topk_draft", "spec_accept_sample", "spec_greedy_tokens",
+                 "moe_active_expert_bytes",
                  "spec_accept", "moe_rmsnorm"):
         getattr(lib, name).restype = i
     _LIB = lib
@@ -199,6 +211,63 @@ def moe_hot_experts(expert_offsets, hot_ids, hot_counts=None, stream=None):
         _ptr(expert_offsets, torch.int32, "expert_offsets"), E, hot_ids.numel(),
         _ptr(hot_ids, torch.int32, "hot_ids"), _ptr(hot_counts, torch.int32, "hot_counts"),
         _stream(stream)), "moe_hot_experts")
+
+
+def moe_affinity_table_workspace_bytes(E):
+    return int(load_library().moe_affinity_table_workspace_bytes(int(E)))
+
+
+def moe_affinity_table(w_gate, w_up, w_down, affinity, workspace, stream=None):
+    E, f, d = w_gate.shape
+    _check(load_library().moe_affinity_table(
+        _ptr(w_gate, None, "w_gate"), _ptr(w_up, w_gate.dtype, "w_up"),
+        _ptr(w_down, w_gate.dtype, "w_down"), E, d, f, _dtype_code(w_gate),
+        _ptr(affinity, torch.float32, "affinity"), _ptr(workspace, None, "workspace"),
+        workspace.numel() * workspace.element_size(), _stream(stream)), "moe_affinity_table")
+
+
+def moe_nearest_draft_expert(affinity, draft_ids, remap, stream=None):
+    E = affinity.shape[0]
+    _check(load_library().moe_nearest_draft_expert(
+        _ptr(affinity, torch.float32, "affinity"), E, _ptr(draft_ids, torch.int32, "draft_ids"),
+        draft_ids.numel(), _ptr(remap, torch.int32, "remap"), _stream(stream)),
+        "moe_nearest_draft_expert")
+
+
+def moe_route_topk_draft(x, w_router, bias, k, renorm, remap, topk_idx, topk_w, stream=None):
+    T, d = x.shape
+    E = w_router.shape[0]
+    _check(load_library().moe_route_topk_draft(
+        _ptr(x, None, "x"), _ptr(w_router, x.dtype, "w_router"),
+        _ptr(bias, torch.float32, "bias"), T, d, E, k, int(bool(renorm)), _dtype_code(x),
+        _ptr(remap, torch.int32, "remap"), _ptr(topk_idx, torch.int32, "topk_idx"),
+        _ptr(topk_w, torch.float32, "topk_w"), _stream(stream)), "moe_route_topk_draft")
+
+
+def spec_accept_sample(draft_ids, p_draft, p_target, u_accept, u_sample, accept_len, out_tokens,
+                       stream=None):
+    B, gp1, V = p_target.shape
+    gamma = gp1 - 1
+    _check(load_library().spec_accept_sample(
+        _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(p_draft, torch.float32, "p_draft"),
+        _ptr(p_target, torch.float32, "p_target"), _ptr(u_accept, torch.float32, "u_accept"),
+        _ptr(u_sample, torch.float32, "u_sample"), B, gamma, V,
+        _ptr(accept_len, torch.int32, "accept_len"), _ptr(out_tokens, torch.int32, "out_tokens"),
+        _stream(stream)), "spec_accept_sample")
+
+
+def spec_greedy_tokens(logits, tokens, stream=None):
+    R, V = logits.shape
+    _check(load_library().spec_greedy_tokens(
+        _ptr(logits, None, "logits"), R, V, _dtype_code(logits),
+        _ptr(tokens, torch.int32, "tokens"), _stream(stream)), "spec_greedy_tokens")
+
+
+def moe_active_expert_bytes(expert_offsets, bytes_per_expert, out_bytes, stream=None):
+    E = expert_offsets.numel() - 1
+    _check(load_library().moe_active_expert_bytes(
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), E, int(bytes_per_expert),
+        _ptr(out_bytes, torch.int64, "out_bytes"), _stream(stream)), "moe_active_expert_bytes")
 
 
 def moe_rmsnorm(x, gain, eps, out, stream=None):

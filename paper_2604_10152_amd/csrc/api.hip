@@ -162,6 +162,77 @@ int moe_hot_experts(const int32_t* expert_offsets, int E, int n_hot, int32_t* ho
                                   (hipStream_t)stream));
 }
 
+size_t moe_affinity_table_workspace_bytes(int E) {
+    if (E < 1 || E > SPECMOE_MAX_EXPERTS) return 0;
+    return affinity_workspace_bytes(E);
+}
+
+int moe_affinity_table(const void* w_gate, const void* w_up, const void* w_down, int E,
+                       int d_model, int d_ff, int dtype, float* affinity, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (E < 1 || E > SPECMOE_MAX_EXPERTS || d_model < 1 || d_ff < 1) return SPECMOE_ERR_SHAPE;
+    // 16-byte loads: one expert matrix must be a whole number of 16-byte chunks
+    if (((size_t)d_model * d_ff * esize(dtype)) % 16 != 0) return SPECMOE_ERR_SHAPE;
+    if (!w_gate || !w_up || !w_down || !affinity || !workspace) return SPECMOE_ERR_NULL;
+    if ((((uintptr_t)w_gate | (uintptr_t)w_up | (uintptr_t)w_down) & 15u) != 0 ||
+        ((uintptr_t)workspace & 7u) != 0)
+        return SPECMOE_ERR_SHAPE;
+    if (workspace_bytes < affinity_workspace_bytes(E)) return SPECMOE_ERR_WORKSPACE;
+    return dev(launch_affinity_table(w_gate, w_up, w_down, E, d_model, d_ff, dtype, affinity,
+                                     workspace, (hipStream_t)stream));
+}
+
+int moe_nearest_draft_expert(const float* affinity, int E, const int32_t* draft_ids, int n_draft,
+                             int32_t* remap, void* stream) {
+    if (E < 1 || E > SPECMOE_MAX_EXPERTS || n_draft < 1 || n_draft > E) return SPECMOE_ERR_SHAPE;
+    if (!affinity || !draft_ids || !remap) return SPECMOE_ERR_NULL;
+    return dev(launch_nearest_draft(affinity, E, draft_ids, n_draft, remap, (hipStream_t)stream));
+}
+
+int moe_route_topk_draft(const void* x, const void* w_router, const float* router_bias, int T,
+                         int d_model, int E, int k, int renorm, int dtype, const int32_t* remap,
+                         int32_t* topk_idx, float* topk_w, void* stream) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (T < 0 || d_model < 1 || E < 1 || E > SPECMOE_MAX_EXPERTS || k < 1 || k > E ||
+        k > SPECMOE_MAX_TOPK || pairs_overflow(T, k))
+        return SPECMOE_ERR_SHAPE;
+    if (!remap) return SPECMOE_ERR_NULL;
+    if (T == 0) return SPECMOE_OK;
+    if (!x || !w_router || !topk_idx || !topk_w) return SPECMOE_ERR_NULL;
+    return dev(launch_route_topk(x, w_router, router_bias, T, d_model, E, k, renorm, dtype,
+                                 topk_idx, topk_w, (hipStream_t)stream, remap));
+}
+
+int spec_accept_sample(const int32_t* draft_ids, const float* p_draft, const float* p_target,
+                       const float* u_accept, const float* u_sample, int B, int gamma, int V,
+                       int32_t* accept_len, int32_t* out_tokens, void* stream) {
+    if (B < 0 || gamma < 0 || gamma > SPECMOE_MAX_GAMMA || V < 1) return SPECMOE_ERR_SHAPE;
+    if ((long long)B * (gamma + 1) > INT_MAX / 2) return SPECMOE_ERR_SHAPE;
+    if (B == 0) return SPECMOE_OK;
+    if (!p_target || !u_sample || !accept_len || !out_tokens) return SPECMOE_ERR_NULL;
+    if (gamma > 0 && (!draft_ids || !p_draft || !u_accept)) return SPECMOE_ERR_NULL;
+    return dev(launch_spec_accept_sample(draft_ids, p_draft, p_target, u_accept, u_sample, B,
+                                         gamma, V, accept_len, out_tokens, (hipStream_t)stream));
+}
+
+int spec_greedy_tokens(const void* logits, int R, int V, int dtype, int32_t* tokens,
+                       void* stream) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (R < 0 || V < 1) return SPECMOE_ERR_SHAPE;
+    if (R == 0) return SPECMOE_OK;
+    if (!logits || !tokens) return SPECMOE_ERR_NULL;
+    return dev(launch_greedy_tokens(logits, R, V, dtype, tokens, (hipStream_t)stream));
+}
+
+int moe_active_expert_bytes(const int32_t* expert_offsets, int E, long long bytes_per_expert,
+                            long long* out_bytes, void* stream) {
+    if (E < 1 || E > SPECMOE_MAX_EXPERTS || bytes_per_expert < 0) return SPECMOE_ERR_SHAPE;
+    if (!expert_offsets || !out_bytes) return SPECMOE_ERR_NULL;
+    return dev(launch_active_expert_bytes(expert_offsets, E, bytes_per_expert, out_bytes,
+                                          (hipStream_t)stream));
+}
+
 int moe_rmsnorm(const void* x, const void* gain, int T, int d_model, float eps, int dtype,
                 void* out, void* stream) {
     if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
@@ -183,6 +254,6 @@ const char* specmoe_status_string(int status) {
     }
 }
 
-int specmoe_abi_version(void) { return 3; }
+int specmoe_abi_version(void) { return 4; }
 
 }  // extern "C"

@@ -42,7 +42,22 @@ __device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + __expf(-
 // ---- launchers (host side, defined in the .hip files) -------------------------------
 hipError_t launch_route_topk(const void* x, const void* wr, const float* bias, int T, int d,
                              int E, int k, int renorm, int dtype, int32_t* idx, float* w,
-                             hipStream_t s);
+                             hipStream_t s, const int32_t* remap = nullptr);
+// speculation phase (draft_route.hip)
+size_t affinity_workspace_bytes(int E);
+hipError_t launch_affinity_table(const void* wg, const void* wu, const void* wd, int E, int d,
+                                 int f, int dtype, float* table, void* workspace, hipStream_t s);
+hipError_t launch_nearest_draft(const float* affinity, int E, const int32_t* draft_ids,
+                                int n_draft, int32_t* remap, hipStream_t s);
+// sampling-based acceptance, greedy head, active-expert volume (spec_sample.hip)
+hipError_t launch_spec_accept_sample(const int32_t* draft, const float* p_draft,
+                                     const float* p_target, const float* u_accept,
+                                     const float* u_sample, int B, int gamma, int V,
+                                     int32_t* accept_len, int32_t* out_tokens, hipStream_t s);
+hipError_t launch_greedy_tokens(const void* logits, int R, int V, int dtype, int32_t* tokens,
+                                hipStream_t s);
+hipError_t launch_active_expert_bytes(const int32_t* offsets, int E, long long bytes_per_expert,
+                                      long long* out, hipStream_t s);
 hipError_t launch_permute(const void* x, const int32_t* idx, int T, int d, int E, int k,
                           int dtype, void* x_perm, int32_t* offsets, int32_t* row_src,
                           int32_t* row_of, hipStream_t s);

@@ -53,7 +53,8 @@ __device__ __forceinline__ bool better(double av, int aid, double bv, int bid) {
 template <typename T, bool VEC, int TOK>
 __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
     const T* __restrict__ x, const T* __restrict__ wr, const float* __restrict__ bias, int Tn,
-    int d, int E, int k, int renorm, int32_t* __restrict__ idx_out, float* __restrict__ w_out) {
+    int d, int E, int k, int renorm, int32_t* __restrict__ idx_out, float* __restrict__ w_out,
+    const int32_t* __restrict__ remap /* nullable: draft-mode expert substitution, [E] */) {
     extern __shared__ double lds_d[];                 // logits[TOK][E], then part[4][TOK][8]
     double* logits = lds_d;
     double* part = lds_d + (size_t)TOK * E;
@@ -151,40 +152,40 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
         if (lane == s) { my_p = p; my_id = bid; }
     }
     if (lane < k) {
-        idx_out[(size_t)t * k + lane] = my_id;
+        idx_out[(size_t)t * k + lane] = remap ? remap[my_id] : my_id;
         w_out[(size_t)t * k + lane] = (float)(renorm ? my_p / wsum_sel : my_p);
     }
 }
 
 template <typename T, bool VEC, int TOK>
 void launch_variant(const T* x, const T* wr, const float* bias, int Tn, int d, int E, int k,
-                    int renorm, int32_t* idx, float* w, hipStream_t s) {
+                    int renorm, int32_t* idx, float* w, const int32_t* remap, hipStream_t s) {
     dim3 grid((Tn + TOK - 1) / TOK), block(kRouteThreads);
     size_t lds = ((size_t)TOK * E + (size_t)kRouteWaves * TOK * kExpertChunk) * sizeof(double);
     hipLaunchKernelGGL((route_topk_kernel<T, VEC, TOK>), grid, block, lds, s, x, wr, bias, Tn, d,
-                       E, k, renorm, idx, w);
+                       E, k, renorm, idx, w, remap);
 }
 
 template <typename T, int V>
 void launch_typed(const void* x, const void* wr, const float* bias, int Tn, int d, int E, int k,
-                  int renorm, int32_t* idx, float* w, hipStream_t s) {
+                  int renorm, int32_t* idx, float* w, const int32_t* remap, hipStream_t s) {
     const bool vec = (d % V == 0) && ((((uintptr_t)x | (uintptr_t)wr) & 15u) == 0);
     const bool many = Tn >= 1024;                     // enough tokens to fill the chip 4 at a time
     const T* xt = (const T*)x;
     const T* wt = (const T*)wr;
-    if (vec && many) launch_variant<T, true, 4>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, s);
-    else if (vec) launch_variant<T, true, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, s);
-    else launch_variant<T, false, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, s);
+    if (vec && many) launch_variant<T, true, 4>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else if (vec) launch_variant<T, true, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else launch_variant<T, false, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
 }
 
 }  // namespace
 
 hipError_t launch_route_topk(const void* x, const void* wr, const float* bias, int T, int d,
                              int E, int k, int renorm, int dtype, int32_t* idx, float* w,
-                             hipStream_t s) {
+                             hipStream_t s, const int32_t* remap) {
     if (T == 0) return hipSuccess;
-    if (dtype == 0) launch_typed<float, 4>(x, wr, bias, T, d, E, k, renorm, idx, w, s);
-    else launch_typed<bf16_t, 8>(x, wr, bias, T, d, E, k, renorm, idx, w, s);
+    if (dtype == 0) launch_typed<float, 4>(x, wr, bias, T, d, E, k, renorm, idx, w, remap, s);
+    else launch_typed<bf16_t, 8>(x, wr, bias, T, d, E, k, renorm, idx, w, remap, s);
     return hipGetLastError();
 }
 

@@ -34,11 +34,19 @@ class MoEVerifyLayer:
         self.h = torch.empty((P, d_ff), dtype=dtype, device=dev)
 
     def forward(self, x, w_router, w_gate, w_up, w_down, bias=None, residual=None, out=None,
-                stream=None, up_events=None):
+                stream=None, up_events=None, draft_remap=None):
         """Enqueues the layer.  `up_events`, if given, is a (start, end) pair of torch events
-        recorded around the gate/up expert GEMM (used by the benchmark's roofline figure)."""
+        recorded around the gate/up expert GEMM (used by the benchmark's roofline figure).
+        `draft_remap` ([E] int32 from moe_nearest_draft_expert) switches to the draft model's
+        routing: selected experts that are not resident are replaced by their nearest draft
+        expert, so only draft experts compute."""
         out = self.out if out is None else out
-        B.moe_route_topk(x, w_router, bias, self.k, self.renorm, self.topk_idx, self.topk_w, stream)
+        if draft_remap is None:
+            B.moe_route_topk(x, w_router, bias, self.k, self.renorm, self.topk_idx, self.topk_w,
+                             stream)
+        else:
+            B.moe_route_topk_draft(x, w_router, bias, self.k, self.renorm, draft_remap,
+                                   self.topk_idx, self.topk_w, stream)
         B.moe_permute(x, self.topk_idx, self.E, None if self.fuse_gather else self.x_perm,
                       self.expert_offsets, self.row_src, self.row_of, stream)
         if up_events is not None:

@@ -29,7 +29,7 @@ def test_header_and_library_agree(lib):
     assert set(declared) == set(binding.EXPORTED_SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.specmoe_abi_version() == 3
+    assert lib.specmoe_abi_version() == 4
 
 
 def test_status_strings(lib):
@@ -121,6 +121,46 @@ def test_combine_accept_rmsnorm_validation(lib):
     assert r(P, P, 4, 8, 1e-5, 2, P, N) == 3
     assert r(P, P, 4, 8, -1.0, 0, P, N) == 2
     assert r(P, N, 4, 8, 1e-5, 0, P, N) == 1
+
+
+def test_speculation_phase_validation(lib):
+    q = lib.moe_affinity_table_workspace_bytes
+    assert q(0) == 0 and q(2000) == 0
+    assert q(8) == 1 * 1024 * 64 * 8 and q(9) == 3 * 1024 * 64 * 8 and q(64) == 36 * 1024 * 64 * 8
+    P16 = ctypes.c_void_p(0x1000)
+    a = lib.moe_affinity_table
+    assert a(P16, P16, P16, 8, 64, 64, 7, P, P, 1 << 30, N) == 3                 # dtype
+    assert a(P16, P16, P16, 0, 64, 64, 1, P, P, 1 << 30, N) == 2                 # E < 1
+    assert a(P16, P16, P16, 8, 3, 5, 1, P, P, 1 << 30, N) == 2                   # 30 bytes per matrix
+    assert a(ctypes.c_void_p(0x1004), P16, P16, 8, 64, 64, 1, P, P, 1 << 30, N) == 2   # alignment
+    assert a(N, P16, P16, 8, 64, 64, 1, P, P, 1 << 30, N) == 1
+    assert a(P16, P16, P16, 8, 64, 64, 1, P, N, 1 << 30, N) == 1
+    assert a(P16, P16, P16, 8, 64, 64, 1, P, P, 100, N) == 4                     # workspace
+    n = lib.moe_nearest_draft_expert
+    assert n(P, 8, P, 0, P, N) == 2 and n(P, 8, P, 9, P, N) == 2 and n(P, 0, P, 1, P, N) == 2
+    assert n(N, 8, P, 2, P, N) == 1 and n(P, 8, N, 2, P, N) == 1 and n(P, 8, P, 2, N, N) == 1
+    r = lib.moe_route_topk_draft
+    assert r(P, P, N, 4, 8, 8, 2, 1, 5, P, P, P, N) == 3
+    assert r(P, P, N, 4, 8, 8, 9, 1, 0, P, P, P, N) == 2
+    assert r(P, P, N, 4, 8, 8, 2, 1, 0, N, P, P, N) == 1                         # remap missing
+    assert r(N, N, N, 0, 8, 8, 2, 1, 0, P, N, N, N) == 0
+
+
+def test_sampling_and_reporting_validation(lib):
+    s = lib.spec_accept_sample
+    assert s(P, P, P, P, P, -1, 3, 10, P, P, N) == 2
+    assert s(P, P, P, P, P, 4, 65, 10, P, P, N) == 2                             # gamma > 64
+    assert s(P, P, P, P, P, 4, 3, 0, P, P, N) == 2
+    assert s(N, P, P, P, P, 4, 3, 10, P, P, N) == 1
+    assert s(P, P, N, P, P, 4, 3, 10, P, P, N) == 1
+    assert s(P, P, P, P, P, 4, 3, 10, N, P, N) == 1
+    assert s(N, N, N, N, N, 0, 3, 10, N, N, N) == 0
+    g = lib.spec_greedy_tokens
+    assert g(P, 4, 10, 3, P, N) == 3 and g(P, -1, 10, 0, P, N) == 2 and g(P, 4, 0, 0, P, N) == 2
+    assert g(N, 4, 10, 0, P, N) == 1 and g(P, 4, 10, 0, N, N) == 1 and g(N, 0, 10, 0, N, N) == 0
+    b = lib.moe_active_expert_bytes
+    assert b(P, 0, 10, P, N) == 2 and b(P, 8, -1, P, N) == 2
+    assert b(N, 8, 10, P, N) == 1 and b(P, 8, 10, N, N) == 1
 
 
 def test_binding_refuses_cpu_tensors():
