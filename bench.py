@@ -5,7 +5,7 @@ A step is one pass of the whole hot path over one batch of synthetic input that 
 resident in HBM: moe_route_topk -> moe_permute -> moe_expert_up_swiglu_gather -> moe_expert_down ->
 moe_combine -> spec_accept.  Prints ONE JSON line (see README / design notes for the fields).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..6] [--no-cpu-baseline]
 """
 import argparse
 import json
@@ -135,7 +135,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6])
     ap.add_argument("--seed", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=["verify", "speculation"], default="verify",

@@ -92,6 +92,12 @@ hipError_t launch_expert_up_bf16_small(const bf16_t* x_perm, const int32_t* offs
 hipError_t launch_expert_down_bf16_small(const bf16_t* h, const int32_t* offsets,
                                          const bf16_t* wd, int n_rows, int d, int f, int E,
                                          bf16_t* y, hipStream_t s);
+hipError_t launch_expert_up_bf16_mid(const bf16_t* x_perm, const int32_t* offsets,
+                                     const bf16_t* wg, const bf16_t* wu, int n_rows, int d, int f,
+                                     int E, bf16_t* h, hipStream_t s, const int32_t* row_src,
+                                     int topk);
+hipError_t launch_expert_down_bf16_mid(const bf16_t* h, const int32_t* offsets, const bf16_t* wd,
+                                       int n_rows, int d, int f, int E, bf16_t* y, hipStream_t s);
 hipError_t launch_combine(const void* y_perm, const int32_t* row_of, const float* w,
                           const void* residual, int T, int d, int k, int dtype, void* out,
                           hipStream_t s);

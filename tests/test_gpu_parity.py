@@ -355,9 +355,10 @@ def test_layer_full_oracle(cfg_id):
     assert torch.equal(out, out2)
 
 
-@pytest.mark.parametrize("cfg_id,n_sample", [(2, 24), (4, 24)])
+@pytest.mark.parametrize("cfg_id,n_sample", [(2, 24), (4, 24), (6, 24)])
 def test_layer_sampled_tokens(cfg_id, n_sample):
-    """Full-size Mixtral-shaped layers in the launch configuration the benchmark times:
+    """Full-size layers (Mixtral shape; Llama-4-Scout shape with top-1 routing, Table I) in the
+    launch configuration the benchmark times:
     routing and permutation checked in full; outputs on a seeded token sample (tokens are
     independent, so the per-token definition applies row by row)."""
     cfg = synth.CONFIGS[cfg_id]
@@ -368,8 +369,9 @@ def test_layer_sampled_tokens(cfg_id, n_sample):
     rng = np.random.default_rng(cfg_id)
     sample = np.sort(rng.choice(cfg.T, size=n_sample, replace=False))
     xs = f64(L["x"][torch.from_numpy(sample).cuda()])
+    bias = None if L["bias"] is None else f64(L["bias"])
     want = orc.moe_layer_brute_force(xs, f64(L["w_router"]), LazyF64(L["w_gate"]),
-                                     LazyF64(L["w_up"]), LazyF64(L["w_down"]), cfg.k, None, cfg.renorm)
+                                     LazyF64(L["w_up"]), LazyF64(L["w_down"]), cfg.k, bias, cfg.renorm)
     got = f64(out[torch.from_numpy(sample).cuda()])
     err = row_rel_err(got, want)
     print(f"   cfg{cfg_id}: sampled-row err={err:.3e}", flush=True)

@@ -65,6 +65,11 @@ CONFIGS = {
     5: MoEConfig("cfg5-32-layer-stack", "bf16", 4096, 14336, 8, 2, 32, 4,
                  x_std=1.0 / math.sqrt(4096), w_std=0.02, router_std=0.02,
                  n_layers=32, match_prob=0.7),
+    # Llama-4-Scout-shaped block (Table I: 16 experts, top-1 routing, skewness 0.59; 218 GB over
+    # 48 layers -> d = 5120, f = 8192).  Zipf exponent 0.53 with unit logit noise puts 59 % of
+    # the tokens on the 4 hottest experts.
+    6: MoEConfig("cfg6-scout-top1", "bf16", 5120, 8192, 16, 1, 256, 7,
+                 x_std=1.0 / math.sqrt(5120), w_std=0.02, router_std=1.0, zipf=0.53),
 }
 
 
