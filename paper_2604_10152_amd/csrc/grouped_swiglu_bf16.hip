@@ -18,6 +18,7 @@
 // 32-row MFMA sub-tiles beyond the expert's last row are skipped (wave-uniform), and waves
 // take sub-tiles interleaved so that a partial tile stays balanced across the SIMDs.
 #include "common.h"
+#include "tile_map.h"
 
 #include <cstdlib>
 #include <type_traits>
@@ -69,29 +70,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_kernel(
 
     // ---- logical tile of this workgroup -------------------------------------------
     const int NT = (N + C::BN_OUT - 1) / C::BN_OUT;
-    int total_mt = 0;
-    for (int e = 0; e < E; ++e) total_mt += (offsets[e + 1] - offsets[e] + C::BM - 1) / C::BM;
-    const long long G = (long long)total_mt * NT;
-    const long long per_xcd = (G + kXcds - 1) / kXcds;
-    const long long slot = blockIdx.x / kXcds;
-    const long long L = (long long)(blockIdx.x % kXcds) * per_xcd + slot;
-    if (slot >= per_xcd || L >= G) return;
-    int expert = 0, row0 = 0, tile_rows = 0, nt = 0;
-    {
-        long long base = 0;
-        for (int e = 0; e < E; ++e) {
-            const int lo = offsets[e], hi = offsets[e + 1];
-            const int mt = (hi - lo + C::BM - 1) / C::BM;
-            if (L < base + (long long)mt * NT) {
-                const long long rem = L - base;
-                nt = (int)(rem / mt);
-                const int mi = (int)(rem - (long long)nt * mt);
-                expert = e; row0 = lo + mi * C::BM; tile_rows = min(C::BM, hi - row0);
-                break;
-            }
-            base += (long long)mt * NT;
-        }
-    }
+    TileLoc t;
+    if (!locate_tile<C::BM>(offsets, E, NT, blockIdx.x, t)) return;
+    const int expert = t.expert, row0 = t.row0, tile_rows = t.tile_rows, nt = t.nt;
     const int n0 = nt * C::BN_OUT;
     const int nsub = (tile_rows + 31) / 32;              // active 32-row sub-tiles
 

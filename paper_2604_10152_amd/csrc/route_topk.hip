@@ -3,11 +3,16 @@
 //
 // A workgroup of 4 wavefronts owns TOK tokens.  The d_model axis is dealt to the 256 lanes in
 // 16-byte chunks (chunk q -> wave (q/64)%4, lane q%64), every lane keeps fp64 partial sums
-// for TOK tokens x 8 experts, so one router-weight load feeds TOK tokens.  Partial sums are
-// reduced with the same xor-butterfly and the same wave order for every expert column: two
-// experts with identical router rows get bit-identical logits and the tie goes to the lower
-// id.  Wave t then ranks token t: the E logits sit in LDS, top-k is k rounds of a wave-wide
-// arg-max on the key (logit descending, expert id ascending).
+// for TOK tokens x EC experts (TOK*EC <= 64), so one router-weight load feeds TOK tokens.
+// The TOK*EC partial sums of a wave are reduced over its 64 lanes by a transposing butterfly:
+// at the step with lane distance h a lane hands the half of its values that its partner keeps
+// to the partner and adds what it receives, so 63 exchange-and-add steps reduce all values at
+// once (a plain butterfly needs 6 per value) and lane l ends up with the total of value l.
+// Every value is summed over the same pairs of lanes in the same order, and fp addition is
+// commutative, so two experts with identical router rows get bit-identical logits and the tie
+// goes to the lower id.  The 4 wave totals are added in fixed order.  Wave t then ranks token
+// t: the E logits sit in LDS, top-k is k rounds of a wave-wide arg-max on the key (logit
+// descending, expert id ascending).
 #include "common.h"
 
 namespace specmoe {
@@ -15,7 +20,28 @@ namespace {
 
 constexpr int kRouteWaves = 4;
 constexpr int kRouteThreads = kRouteWaves * kWave;
-constexpr int kExpertChunk = 8;     // expert columns accumulated per pass over x
+
+// Transposing butterfly over the 64 lanes of a wave: v[0..CNT) in every lane -> v[0] = total of
+// value (lane * CNT0 / 64) where CNT0 is the count at the first step.
+template <int CNT, int BIT>
+struct TransposeReduce {
+    __device__ __forceinline__ static void run(double* v, int lane) {
+        if constexpr (CNT > 1) {
+            constexpr int H = CNT / 2;
+            const bool up = (lane & BIT) != 0;
+#pragma unroll
+            for (int i = 0; i < H; ++i) {
+                const double send = up ? v[i] : v[i + H];
+                const double keep = up ? v[i + H] : v[i];
+                v[i] = keep + __shfl_xor(send, BIT, kWave);
+            }
+            if constexpr (BIT > 1) TransposeReduce<H, BIT / 2>::run(v, lane);
+        } else {
+            v[0] += __shfl_xor(v[0], BIT, kWave);
+            if constexpr (BIT > 1) TransposeReduce<1, BIT / 2>::run(v, lane);
+        }
+    }
+};
 
 template <typename T, bool VEC> struct Chunk;
 template <> struct Chunk<float, true> {
@@ -50,63 +76,65 @@ __device__ __forceinline__ bool better(double av, int aid, double bv, int bid) {
     return (av > bv) || (av == bv && aid < bid);
 }
 
-template <typename T, bool VEC, int TOK>
+template <typename T, bool VEC, int TOK, int EC>
 __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
     const T* __restrict__ x, const T* __restrict__ wr, const float* __restrict__ bias, int Tn,
     int d, int E, int k, int renorm, int32_t* __restrict__ idx_out, float* __restrict__ w_out,
     const int32_t* __restrict__ remap /* nullable: draft-mode expert substitution, [E] */) {
-    extern __shared__ double lds_d[];                 // logits[TOK][E], then part[4][TOK][8]
+    static_assert(TOK * EC <= kWave && (TOK * EC & (TOK * EC - 1)) == 0, "values per wave");
+    constexpr int NV = TOK * EC;                      // partial sums per lane and pass
+    extern __shared__ double lds_d[];                 // logits[TOK][E], then part[4][NV]
     double* logits = lds_d;
     double* part = lds_d + (size_t)TOK * E;
     typedef Chunk<T, VEC> CH;
     constexpr int V = CH::N;
+    constexpr int G = EC < 8 ? EC : 8;                // router rows loaded together
     const int lane = threadIdx.x % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int t0 = blockIdx.x * TOK;
     const int nq = d / V;                             // chunks per row (VEC: d % V == 0)
 
-    for (int e0 = 0; e0 < E; e0 += kExpertChunk) {
-        double acc[TOK][kExpertChunk];
+    for (int e0 = 0; e0 < E; e0 += EC) {
+        double acc[NV];                               // index t * EC + c
 #pragma unroll
-        for (int t = 0; t < TOK; ++t)
-#pragma unroll
-            for (int c = 0; c < kExpertChunk; ++c) acc[t][c] = 0.0;
+        for (int i = 0; i < NV; ++i) acc[i] = 0.0;
         for (int q = threadIdx.x; q < nq; q += kRouteThreads) {
-            typename CH::Raw xr[TOK], wraw[kExpertChunk];
+            typename CH::Raw xr[TOK];
 #pragma unroll
             for (int t = 0; t < TOK; ++t)
                 xr[t] = CH::load(x + (size_t)min(t0 + t, Tn - 1) * d + (size_t)q * V);
-#pragma unroll
-            for (int c = 0; c < kExpertChunk; ++c)
-                wraw[c] = CH::load(wr + (size_t)min(e0 + c, E - 1) * d + (size_t)q * V);
             double xv[TOK][V];
 #pragma unroll
             for (int t = 0; t < TOK; ++t) CH::widen(xr[t], xv[t]);
 #pragma unroll
-            for (int c = 0; c < kExpertChunk; ++c) {
-                double wv[V];
-                CH::widen(wraw[c], wv);
+            for (int c0 = 0; c0 < EC; c0 += G) {
+                typename CH::Raw wraw[G];
 #pragma unroll
-                for (int t = 0; t < TOK; ++t)
+                for (int c = 0; c < G; ++c)
+                    wraw[c] = CH::load(wr + (size_t)min(e0 + c0 + c, E - 1) * d + (size_t)q * V);
 #pragma unroll
-                    for (int i = 0; i < V; ++i) acc[t][c] = fma(xv[t][i], wv[i], acc[t][c]);
+                for (int c = 0; c < G; ++c) {
+                    double wv[V];
+                    CH::widen(wraw[c], wv);
+#pragma unroll
+                    for (int t = 0; t < TOK; ++t)
+#pragma unroll
+                        for (int i = 0; i < V; ++i)
+                            acc[t * EC + c0 + c] = fma(xv[t][i], wv[i], acc[t * EC + c0 + c]);
+                }
             }
         }
-        // lanes -> wave total (butterfly), waves -> workgroup total (fixed order 0,1,2,3)
-#pragma unroll
-        for (int t = 0; t < TOK; ++t)
-#pragma unroll
-            for (int c = 0; c < kExpertChunk; ++c) {
-                const double s = wave_sum(acc[t][c]);
-                if (lane == 0) part[(wave * TOK + t) * kExpertChunk + c] = s;
-            }
+        // lanes -> wave totals (transposing butterfly), waves -> workgroup total (order 0,1,2,3)
+        TransposeReduce<NV, kWave / 2>::run(acc, lane);
+        constexpr int REP = kWave / NV;               // lanes holding the same value
+        if (lane % REP == 0) part[wave * NV + lane / REP] = acc[0];
         __syncthreads();
-        for (int i = threadIdx.x; i < TOK * kExpertChunk; i += kRouteThreads) {
-            const int t = i / kExpertChunk, c = i % kExpertChunk;
+        if (threadIdx.x < NV) {
+            const int t = threadIdx.x / EC, c = threadIdx.x % EC;
             if (e0 + c < E) {
-                double s = part[(0 * TOK + t) * kExpertChunk + c];
+                double s = part[threadIdx.x];
 #pragma unroll
-                for (int w = 1; w < kRouteWaves; ++w) s += part[(w * TOK + t) * kExpertChunk + c];
+                for (int w = 1; w < kRouteWaves; ++w) s += part[w * NV + threadIdx.x];
                 logits[(size_t)t * E + e0 + c] = s + (bias ? (double)bias[e0 + c] : 0.0);
             }
         }
@@ -157,13 +185,27 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
     }
 }
 
-template <typename T, bool VEC, int TOK>
+template <typename T, bool VEC, int TOK, int EC>
 void launch_variant(const T* x, const T* wr, const float* bias, int Tn, int d, int E, int k,
                     int renorm, int32_t* idx, float* w, const int32_t* remap, hipStream_t s) {
     dim3 grid((Tn + TOK - 1) / TOK), block(kRouteThreads);
-    size_t lds = ((size_t)TOK * E + (size_t)kRouteWaves * TOK * kExpertChunk) * sizeof(double);
-    hipLaunchKernelGGL((route_topk_kernel<T, VEC, TOK>), grid, block, lds, s, x, wr, bias, Tn, d,
-                       E, k, renorm, idx, w, remap);
+    size_t lds = ((size_t)TOK * E + (size_t)kRouteWaves * TOK * EC) * sizeof(double);
+    hipLaunchKernelGGL((route_topk_kernel<T, VEC, TOK, EC>), grid, block, lds, s, x, wr, bias, Tn,
+                       d, E, k, renorm, idx, w, remap);
+}
+
+// experts per pass: the smallest of 8/16/32/64 that covers E (64 for more), capped at 64/TOK
+template <typename T, bool VEC, int TOK>
+void launch_by_experts(const T* x, const T* wr, const float* bias, int Tn, int d, int E, int k,
+                       int renorm, int32_t* idx, float* w, const int32_t* remap, hipStream_t s) {
+    if (E <= 8 || TOK * 16 > kWave)
+        launch_variant<T, VEC, TOK, (TOK * 8 <= kWave ? 8 : kWave / TOK)>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else if (E <= 16 || TOK * 32 > kWave)
+        launch_variant<T, VEC, TOK, (TOK * 16 <= kWave ? 16 : kWave / TOK)>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else if (E <= 32 || TOK * 64 > kWave)
+        launch_variant<T, VEC, TOK, (TOK * 32 <= kWave ? 32 : kWave / TOK)>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else
+        launch_variant<T, VEC, TOK, kWave / TOK>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
 }
 
 template <typename T, int V>
@@ -173,9 +215,9 @@ void launch_typed(const void* x, const void* wr, const float* bias, int Tn, int 
     const bool many = Tn >= 1024;                     // enough tokens to fill the chip 4 at a time
     const T* xt = (const T*)x;
     const T* wt = (const T*)wr;
-    if (vec && many) launch_variant<T, true, 4>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
-    else if (vec) launch_variant<T, true, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
-    else launch_variant<T, false, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    if (vec && many) launch_by_experts<T, true, 4>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else if (vec) launch_by_experts<T, true, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else launch_by_experts<T, false, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
 }
 
 }  // namespace

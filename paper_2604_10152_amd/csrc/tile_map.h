@@ -19,34 +19,6 @@ struct TileLoc {
     int nt;          // n-tile index
 };
 
-template <int BM>
-__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets, int E, int NT,
-                                            unsigned block_id, TileLoc& t) {
-    int total_mt = 0;
-    for (int e = 0; e < E; ++e) total_mt += (offsets[e + 1] - offsets[e] + BM - 1) / BM;
-    const long long G = (long long)total_mt * NT;
-    const long long per_xcd = (G + kXcds - 1) / kXcds;
-    const long long slot = block_id / kXcds;
-    const long long L = (long long)(block_id % kXcds) * per_xcd + slot;
-    if (slot >= per_xcd || L >= G) return false;
-    long long base = 0;
-    for (int e = 0; e < E; ++e) {
-        const int lo = offsets[e], hi = offsets[e + 1];
-        const int mt = (hi - lo + BM - 1) / BM;
-        if (L < base + (long long)mt * NT) {
-            const long long rem = L - base;
-            t.nt = (int)(rem / mt);
-            const int mi = (int)(rem - (long long)t.nt * mt);
-            t.expert = e;
-            t.row0 = lo + mi * BM;
-            t.tile_rows = min(BM, hi - t.row0);
-            return true;
-        }
-        base += (long long)mt * NT;
-    }
-    return false;
-}
-
 // Even split: an expert with M rows gets ceil(M / BM_MAX) m-tiles of equal height (rounded up
 // to the 32-row MFMA granule), so no tile is a thin remainder that would stream a whole
 // weight tile for a handful of rows.
@@ -70,15 +42,29 @@ __device__ __forceinline__ EvenSplit even_split(int M) {
 // tile index.  Every wave of the workgroup calls this with all 64 lanes active and gets the same
 // answer; a scalar walk over the experts costs several microseconds of integer divisions per
 // workgroup, this one memory round trip and ~100 vector instructions.
-template <int BM_MAX, int GRAN = 32>
-__device__ __forceinline__ bool locate_tile_even(const int32_t* __restrict__ offsets, int E,
+template <int BM_MAX, int GRAN>
+struct EvenPolicy {
+    __device__ __forceinline__ static EvenSplit of(int M) { return even_split<BM_MAX, GRAN>(M); }
+};
+// fixed tile height BM: ceil(M / BM) tiles, the last one ragged
+template <int BM>
+struct FixedPolicy {
+    __device__ __forceinline__ static EvenSplit of(int M) {
+        EvenSplit s{0, BM};
+        if (M > 0) s.mt = (M + BM - 1) / BM;
+        return s;
+    }
+};
+
+template <typename Split>
+__device__ __forceinline__ bool locate_tile_impl(const int32_t* __restrict__ offsets, int E,
                                                  int NT, unsigned block_id, TileLoc& t) {
     const int lane = threadIdx.x % kWave;
     int total_mt = 0;
     for (int e0 = 0; e0 < E; e0 += kWave) {
         const int e = e0 + lane;
         const int M = e < E ? offsets[e + 1] - offsets[e] : 0;
-        total_mt += wave_sum(even_split<BM_MAX, GRAN>(M).mt);
+        total_mt += wave_sum(Split::of(M).mt);
     }
     const long long G = (long long)total_mt * NT;
     const long long per_xcd = (G + kXcds - 1) / kXcds;
@@ -90,7 +76,7 @@ __device__ __forceinline__ bool locate_tile_even(const int32_t* __restrict__ off
     for (int e0 = 0; e0 < E && expert < 0; e0 += kWave) {
         const int e = e0 + lane;
         const int lo = e < E ? offsets[e] : 0, hi = e < E ? offsets[e + 1] : 0;
-        const EvenSplit sp = even_split<BM_MAX, GRAN>(hi - lo);
+        const EvenSplit sp = Split::of(hi - lo);
         int incl = sp.mt;                         // inclusive scan of mt over the lanes
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
@@ -119,6 +105,17 @@ __device__ __forceinline__ bool locate_tile_even(const int32_t* __restrict__ off
     t.tile_rows = __builtin_amdgcn_readfirstlane(rows);
     t.nt = __builtin_amdgcn_readfirstlane(nt);
     return t.expert >= 0;
+}
+
+template <int BM_MAX, int GRAN = 32>
+__device__ __forceinline__ bool locate_tile_even(const int32_t* __restrict__ offsets, int E,
+                                                 int NT, unsigned block_id, TileLoc& t) {
+    return locate_tile_impl<EvenPolicy<BM_MAX, GRAN>>(offsets, E, NT, block_id, t);
+}
+template <int BM>
+__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets, int E, int NT,
+                                            unsigned block_id, TileLoc& t) {
+    return locate_tile_impl<FixedPolicy<BM>>(offsets, E, NT, block_id, t);
 }
 
 // Upper bound of the grid (host side): sum_e ceil(M_e/BM) <= floor(n_rows/BM) + E.

@@ -247,8 +247,10 @@ def test_grouped_fp32(d, f, rows):
 
 
 @pytest.mark.parametrize("d,f,rows", [
-    (256, 384, [300, 0, 37, 1, 513, 256]),           # large-batch tiles: full, ragged, empty
+    (256, 384, [300, 0, 37, 1, 513, 256, 330]),      # large-batch tiles: full, ragged, empty
     (512, 1408, [700, 650]),
+    (4096, 256, [100, 0, 60, 129, 1, 170]),          # mid tier (128-row tiles) in the gate/up GEMM
+    (256, 4096, [100, 0, 60, 129, 1, 170]),          # mid tier in the down GEMM
     (256, 384, [3, 0, 70, 1, 129, 64, 0, 0]),        # few rows per expert: narrow tiles
     (2048, 1408, [0, 40, 1, 0, 310, 7, 0, 22]),      # cfg-3 shape, skewed
     (64, 64, [1]),
@@ -261,10 +263,10 @@ def test_grouped_bf16(d, f, rows):
 def test_expert_up_alone_matches_swiglu_definition():
     """h = silu(x Wg^T) * (x Wu^T) checked on its own (the gate/up GEMM with its epilogue)."""
     _say("expert up only")
-    rows = [200, 0, 61, 300]
+    rows = [200, 0, 61, 300, 420]          # 196 rows per expert on average: large-batch kernel
     off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
     g = torch.Generator().manual_seed(77)
-    d, f, E = 256, 384, 4
+    d, f, E = 256, 384, len(rows)
     xp = (torch.randn(off[-1], d, generator=g) / 16).to(torch.bfloat16)
     wg = torch.randn(E, f, d, generator=g).to(torch.bfloat16)
     wu = torch.randn(E, f, d, generator=g).to(torch.bfloat16)
