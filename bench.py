@@ -141,6 +141,10 @@ def main():
     ap.add_argument("--mode", choices=["verify", "speculation"], default="verify",
                     help="verify (default): the MoE verify layer, the line the harness reads; "
                          "speculation: per-kernel timings of the draft-routing / sampling rows")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step from a captured HIP graph (one launch per step); the "
+                         "gate/up kernel time for the roofline then comes from an eager pass "
+                         "run right after the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one 1 GiB device copy (a kernel of known "
                          "traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE against)")
@@ -195,12 +199,33 @@ def main():
         step()
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
               for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(events[i])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.graph:
+        if stacked:
+            graphed = sm.GraphedStep(lambda st: (stack.forward(x0, layers, stream=st),
+                                                 sm.spec_accept(draft_d, target_d, alen, toks, st)))
+        else:
+            graphed = sm.GraphedStep(lambda st: (
+                layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
+                              stream=st),
+                sm.spec_accept(draft_d, target_d, alen, toks, st)))
+        for _ in range(max(1, args.warmup // 2)):
+            graphed.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphed.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(args.steps):            # kernel time for the roofline: eager, untimed
+            step(events[i])
+        torch.cuda.synchronize()
+    else:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(events[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     up_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
 
@@ -251,6 +276,7 @@ def main():
         "config": {"workload": cfg.name, "B": cfg.B, "gamma": cfg.gamma, "tokens": cfg.T,
                    "d_model": d, "d_ff": f, "experts": cfg.E, "top_k": cfg.k,
                    "active_experts": active, "max_rows_per_expert": int(counts.max())},
+        "launch": "hip-graph" if args.graph else "eager",
         "tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else None,
         "roofline": roof,
     }

@@ -7,4 +7,4 @@ from .binding import (  # noqa: F401
     moe_affinity_table, moe_affinity_table_workspace_bytes, moe_nearest_draft_expert,
     moe_route_topk_draft, spec_accept_sample, spec_greedy_tokens, moe_active_expert_bytes,
 )
-from .layer import MoEVerifyLayer, MoEVerifyStack  # noqa: F401
+from .layer import GraphedStep, MoEVerifyLayer, MoEVerifyStack  # noqa: F401

@@ -472,3 +472,48 @@ def test_stack_full_32_layers_one_token():
     cfg = synth.CONFIGS[5]
     _say("stack cfg5 full: 32 layers, 1 sampled token")
     _check_stack(cfg, n_layers=32, n_sample=1, seed=5)
+
+
+def test_graph_replay_equals_eager():
+    """The multi-layer step captured in a HIP graph: every replay (with eager work and
+    synchronisations in between, and with the input refreshed in place) must reproduce the
+    eager result bit for bit."""
+    _say("HIP graph replay of a 3-layer stack + spec_accept")
+    cfg = synth.MoEConfig("graph", "bf16", 256, 384, 8, 2, 12, 3, 1.0, 0.05, 0.5, n_layers=3,
+                          match_prob=0.6)
+    x, layers = synth.make_stack(cfg, "cuda", seed=9)
+    draft, target = synth.make_tokens(cfg, seed=9)
+    draft, target = draft.cuda(), target.cuda()
+    stack = sm.MoEVerifyStack(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype)
+    alen = torch.empty((cfg.B,), dtype=I32, device="cuda")
+    toks = torch.empty((cfg.B, cfg.gamma + 1), dtype=I32, device="cuda")
+    result = {}
+
+    def step(stream):
+        result["out"] = stack.forward(x, layers, stream=stream)
+        sm.spec_accept(draft, target, alen, toks, stream)
+
+    step(None)
+    torch.cuda.synchronize()
+    eager0 = result["out"].clone()
+    alen0 = alen.clone()
+    g = sm.GraphedStep(step)
+    out_buf = result["out"]                       # the buffer the captured step writes
+    x_alt = (x.float() * 0.5 + 0.1).to(x.dtype)
+    x_orig = x.clone()
+    for rep in range(4):
+        use_alt = rep % 2 == 1
+        x.copy_(x_alt if use_alt else x_orig)
+        out_buf.fill_(float("nan"))
+        alen.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = out_buf.clone()
+        # eager reference for the same input, computed after the replay
+        step(None)
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(torch.int16), result["out"].view(torch.int16)), rep
+        assert torch.equal(alen, alen0)
+        if not use_alt:
+            assert torch.equal(got.view(torch.int16), eager0.view(torch.int16))
