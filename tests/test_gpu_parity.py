@@ -98,6 +98,11 @@ def _check_route(x, wr, bias, k, renorm):
     (torch.bfloat16, 130, 192, 130, 7, True, True),    # more experts than lanes
     (torch.bfloat16, 50, 72, 16, 16, False, False),    # k = E
     (torch.bfloat16, 2048, 4096, 8, 2, True, False),
+    (torch.bfloat16, 3, 64, 1024, 64, True, True),     # the largest E and k the ABI admits
+    (torch.bfloat16, 1500, 128, 20, 2, True, True),    # 4 tokens per workgroup, two expert passes
+    (torch.float32, 1100, 40, 9, 2, True, False),      # 4 tokens per workgroup, fp32, odd E
+    (torch.bfloat16, 40, 256, 24, 4, True, False),     # 32 experts per pass
+    (torch.bfloat16, 2048, 5120, 16, 1, True, True),   # top-1, 16 experts
 ])
 def test_route_cases(dtype, T, d, E, k, renorm, bias):
     _say(f"route {dtype} T={T} d={d} E={E} k={k}")
@@ -118,6 +123,19 @@ def test_route_ties_go_to_lower_expert_id():
     eidx, _, logits = orc.route_topk(f64(x), f64(wr), 12)
     assert (logits[:, 7] == logits[:, 2]).all()
     assert (idx == eidx).all()
+    # duplicated rows that meet in different lanes / different passes of the reduction, in the
+    # 4-tokens-per-workgroup variant (T >= 1024) and with more experts than one pass holds
+    for T2, E2, dup in ((1100, 12, [(7, 2), (11, 2), (5, 0)]), (1100, 40, [(33, 1), (17, 1), (39, 20)]),
+                        (70, 100, [(99, 3), (64, 63), (65, 0)])):
+        x2 = torch.randn(T2, 256, generator=g).to(torch.bfloat16)
+        wr2 = torch.randn(E2, 256, generator=g).to(torch.bfloat16)
+        for a, b in dup:
+            wr2[a] = wr2[b]
+        k2 = min(E2, 12)
+        idx2, _ = _gpu_route(x2, wr2, None, k2, True)
+        eidx2, _, lg2 = orc.route_topk(f64(x2), f64(wr2), k2)
+        assert all((lg2[:, a] == lg2[:, b]).all() for a, b in dup)
+        assert (idx2 == eidx2).all(), (T2, E2)
     x0 = torch.zeros(4, 512, dtype=torch.bfloat16)       # all logits equal
     idx0, w0 = _gpu_route(x0, wr, None, 3, True)
     assert (idx0 == np.array([0, 1, 2])).all() and np.allclose(w0, 1 / 3, rtol=1e-6)
