@@ -3,14 +3,16 @@
 // routed to an expert are multiplied with its weights.)
 //
 // This mode exists for the 1e-5 parity configuration; every load is bounds-checked so any
-// d_model / d_ff works.  A workgroup owns a 64x64 output tile of one expert; the m-tile ->
+// d_model / d_ff works.  A workgroup owns a 64x64 output tile of one expert (64 contraction
+// elements per step, the next step's operands prefetched into registers); the m-tile ->
 // expert lookup walks expert_offsets on the device, so no host read-back is needed.
 #include "common.h"
 
 namespace specmoe {
 namespace {
 
-constexpr int kBM = 64, kBN = 64, kBK = 16, kThreads = 256;
+constexpr int kBM = 64, kBN = 64, kBK = 64, kThreads = 256;
+constexpr int kLd = kBM * kBK / kThreads;     // elements of each operand tile per thread
 
 // Finds the expert and the first row of global m-tile `mt` (tiles never straddle experts).
 __device__ __forceinline__ bool locate_tile(const int32_t* offsets, int E, int mt, int bm,
@@ -44,19 +46,38 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_f32_kernel(
     const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
     float acc0[4][4] = {}, acc1[4][4] = {};
 
-    for (int k0 = 0; k0 < K; k0 += kBK) {
+    // the k-tile after the current one travels from global memory into registers while the
+    // current one is multiplied (one exposed memory round trip per tile instead of two)
+    float ra[kLd], rb0[kLd], rb1[kSwiglu ? kLd : 1];
+    size_t arow[kLd];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int flat = tid + i * kThreads;       // 64 rows x 16 k
+    for (int i = 0; i < kLd; ++i) {
+        const int gr = row0 + (tid + i * kThreads) / kBK;
+        arow[i] = (row_src && gr < row_end) ? (size_t)(row_src[gr] / topk) : (size_t)gr;
+    }
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < kLd; ++i) {
+            const int flat = tid + i * kThreads;       // 64 rows x kBK contraction elements
             const int r = flat / kBK, kk = flat % kBK;
             const int gr = row0 + r, gk = k0 + kk, gn = n0 + r;
-            // with row_src the activation rows are gathered from the token matrix on the fly
-            const size_t ar = (row_src && gr < row_end) ? (size_t)(row_src[gr] / topk) : (size_t)gr;
-            As[kk][r] = (gr < row_end && gk < K) ? A[ar * K + gk] : 0.f;
-            B0s[kk][r] = (gn < N && gk < K) ? w0[(size_t)gn * K + gk] : 0.f;
-            if (kSwiglu) B1s[kk][r] = (gn < N && gk < K) ? w1[(size_t)gn * K + gk] : 0.f;
+            ra[i] = (gr < row_end && gk < K) ? A[arow[i] * K + gk] : 0.f;
+            rb0[i] = (gn < N && gk < K) ? w0[(size_t)gn * K + gk] : 0.f;
+            if (kSwiglu) rb1[i] = (gn < N && gk < K) ? w1[(size_t)gn * K + gk] : 0.f;
+        }
+    };
+    gload(0);
+    for (int k0 = 0; k0 < K; k0 += kBK) {
+#pragma unroll
+        for (int i = 0; i < kLd; ++i) {
+            const int flat = tid + i * kThreads;
+            const int r = flat / kBK, kk = flat % kBK;
+            As[kk][r] = ra[i];
+            B0s[kk][r] = rb0[i];
+            if (kSwiglu) B1s[kk][r] = rb1[i];
         }
         __syncthreads();
+        if (k0 + kBK < K) gload(k0 + kBK);
 #pragma unroll
         for (int kk = 0; kk < kBK; ++kk) {
             float a[4], b0[4], b1[4];
