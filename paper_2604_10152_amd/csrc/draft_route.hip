@@ -137,21 +137,25 @@ __global__ __launch_bounds__(kAffThreads) void affinity_partial_kernel(
     }
 }
 
-__global__ __launch_bounds__(256) void affinity_finish_kernel(const double* __restrict__ partial,
-                                                              int E, int groups,
-                                                              float* __restrict__ table) {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= E * E) return;
+// One wavefront per table entry: lane l adds partials l, l+64, ... in order, then a butterfly.
+__global__ __launch_bounds__(kWave) void affinity_finish_kernel(const double* __restrict__ partial,
+                                                                int E, int groups,
+                                                                float* __restrict__ table) {
+    const int idx = blockIdx.x;
     const int i = idx / E, j = idx % E;
-    if (i == j) { table[idx] = 0.f; return; }
+    if (i == j) {
+        if (threadIdx.x == 0) table[idx] = 0.f;
+        return;
+    }
     const int lo = min(i, j), hi = max(i, j);          // one sum serves both (i,j) and (j,i)
     const int nb = n_blocks(E);
     const int bp = pair_index(lo / kEB, hi / kEB, nb);
     const int slot = (lo % kEB) * kEB + (hi % kEB);
     double s = 0.0;
-    for (int g = 0; g < groups; ++g)
+    for (int g = threadIdx.x; g < groups; g += kWave)
         s += partial[((size_t)bp * groups + g) * (kEB * kEB) + slot];
-    table[idx] = (float)sqrt(s);
+    s = wave_sum(s);
+    if (threadIdx.x == 0) table[idx] = (float)sqrt(s);
 }
 
 // remap[e] = e for a draft expert, else the draft expert with the smallest D[e, .]; equal
@@ -206,8 +210,8 @@ hipError_t launch_affinity_table(const void* wg, const void* wu, const void* wd,
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(affinity_finish_kernel, dim3((E * E + 255) / 256), dim3(256), 0, s, partial,
-                       E, kAffGroups, table);
+    hipLaunchKernelGGL(affinity_finish_kernel, dim3(E * E), dim3(kWave), 0, s, partial, E,
+                       kAffGroups, table);
     return hipGetLastError();
 }
 
