@@ -280,6 +280,43 @@ def main():
         "tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else None,
         "roofline": roof,
     }
+    if args.config == 4 and not args.graph:
+        # same weights, the 80-token batch of the Mixtral-shaped configuration (B=16, gamma=4):
+        # the memory-bound end of the same layer, reported beside the headline workload
+        c2 = synth.CONFIGS[2]
+        x2 = L["x"][:c2.T].contiguous()
+        lay2 = sm.MoEVerifyLayer(c2.T, d, f, cfg.E, cfg.k, cfg.torch_dtype, renorm=cfg.renorm)
+        d2, t2 = synth.make_tokens(c2, seed=args.seed)
+        d2, t2 = d2.cuda(), t2.cuda()
+        al2 = torch.empty(c2.B, dtype=torch.int32, device="cuda")
+        tk2 = torch.empty(c2.B, c2.gamma + 1, dtype=torch.int32, device="cuda")
+        ev2 = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps)]
+
+        def step2(ev=None):
+            lay2.forward(x2, L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
+                         stream=stream, up_events=ev)
+            sm.spec_accept(d2, t2, al2, tk2, stream)
+
+        for _ in range(args.warmup):
+            step2()
+        torch.cuda.synchronize()
+        ta = time.perf_counter()
+        for i in range(args.steps):
+            step2(ev2[i])
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - ta) * 1e3 / args.steps
+        up2 = sum(a.elapsed_time(b) for a, b in ev2) / args.steps
+        act2 = int(((lay2.expert_offsets[1:] - lay2.expert_offsets[:-1]) > 0).sum())
+        bytes2 = (act2 * 2 * d * f + c2.T * d + c2.P * f) * esize
+        out["also"] = {c2.name: {
+            "tokens": c2.T, "ms_per_step": ms2, "tokens_per_s": c2.T / (ms2 * 1e-3),
+            "tflops": c2.flops() / (ms2 * 1e-3) / 1e12,
+            "roofline": {"bound": "hbm", "achieved": bytes2 / (up2 * 1e-3) / 1e9,
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": bytes2 / (up2 * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                         "kernel": "grouped_gemm_bf16_pipe_kernel<PipeCfg<64,128,64,4,1,2,true>> "
+                                   "(gate/up + SwiGLU)", "kernel_ms": up2}}}
     if stacked:
         out["config"]["layers"] = cfg.n_layers
         out["accepted_tokens_per_s"] = float(alen.sum().item()) / (ms_per_step * 1e-3)
