@@ -93,17 +93,19 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
     const int KT = K / C::BK;                    // even: the ABI requires K % 64 == 0
     auto issue_one = [&](int which, int kt, int buf) __attribute__((always_inline)) {
         if ((PROBE & 2) && kt >= C::STAGES - 1) return;
-        const size_t kb = (size_t)min(kt, KT - 1) * C::ROW_BYTES;   // clamped: tail re-loads
+        // the k offset rides in the per-lane offset (one vector add per load); the base
+        // pointers stay loop-invariant scalars.  Clamped: the last steps re-load stage KT-1.
+        const uint32_t kb = (uint32_t)min(kt, KT - 1) * C::ROW_BYTES;
         const uint32_t sbase = lds_base + (uint32_t)buf * C::STAGE_BYTES + wave * 1024u;
 #pragma unroll
         for (int jj = 0; jj < C::A_PW; ++jj)
             if (which == jj && jj < a_cnt)
-                dma16(a_base + kb, a_off[jj], sbase + jj * C::NWAVES * 1024u);
+                dma16(a_base, a_off[jj] + kb, sbase + jj * C::NWAVES * 1024u);
 #pragma unroll
         for (int jj = 0; jj < C::B_PW; ++jj) {
             const bool up = C::SWIGLU && (jj * C::NWAVES * C::ROWS_PER_DMA >= C::BN / 2);
             if (which == C::A_PW + jj)
-                dma16((up ? w1 : w0) + kb, b_off[jj], sbase + C::A_BYTES + jj * C::NWAVES * 1024u);
+                dma16(up ? w1 : w0, b_off[jj] + kb, sbase + C::A_BYTES + jj * C::NWAVES * 1024u);
         }
     };
 
