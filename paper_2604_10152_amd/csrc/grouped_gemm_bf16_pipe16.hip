@@ -16,6 +16,7 @@
 // between two register sets, hence the k loop is unrolled by two.
 #include "pipe_common.h"
 
+#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -29,7 +30,7 @@ __device__ __forceinline__ void dispatch_count(int n, F& f, std::integer_sequenc
     ((n == Is ? (f(std::integral_constant<int, Is>{}), 0) : 0), ...);
 }
 
-template <typename C, int PROBE = 0>
+template <typename C, int PROBE = 0, int SCHED = 1>
 __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
     const bf16_t* __restrict__ A,        // [n_rows, K]
     const int32_t* __restrict__ offsets, // [E+1]
@@ -123,6 +124,51 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
     const int ta = min(TM16, max(0, (nsub - wm + C::WM - 1) / C::WM));   // active A sub-tiles
     const int vm_allow = (C::STAGES - 3) * (a_cnt + C::B_PW);
 
+    // epilogue: SwiGLU tiles are staged in LDS and written as whole rows by the workgroup,
+    // plain tiles go straight to global memory, 8 bytes (4 columns) per lane.  acc[i] is the
+    // wave's i-th A sub-tile (tile rows 16 * (wm + WM * i) ..).
+    auto epilogue = [&](auto& acc, auto ta_tag) __attribute__((always_inline)) {
+        constexpr int TA = decltype(ta_tag)::value;
+        wait_vmcnt<0>();                           // no load may outlive the workgroup's LDS
+
+        const int mrow = lane & 15, cq = (lane >> 4) * 4;
+        if (C::SWIGLU) __builtin_amdgcn_s_barrier();   // every wave's loads have landed
+#pragma unroll
+        for (int i = 0; i < TA; ++i) {
+            const int trow = 16 * (wm + C::WM * i) + mrow;
+            if (!C::SWIGLU && trow >= tile_rows) continue;
+            bf16_t* crow = Cout + (size_t)(row0 + trow) * N;
+            constexpr int JN = C::SWIGLU ? TN16 / 2 : TN16;
+#pragma unroll
+            for (int j = 0; j < JN; ++j) {
+                const int ctile = 16 * (wn * JN + j) + cq;            // column inside the tile
+                float v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (C::SWIGLU) {
+                        const float gt = acc[i][j][q], up = acc[i][j + JN][q];
+                        v[q] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up;
+                    } else {
+                        v[q] = acc[i][j][q];
+                    }
+                }
+                const uint2 pk = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                if (C::SWIGLU) {
+                    *reinterpret_cast<uint2*>(lds_raw + trow * kStageRowBytes + ctile * 2) = pk;
+                } else {
+                    const int col = n0 + ctile;
+                    if (col + 3 < N) {
+                        *reinterpret_cast<uint2*>(crow + col) = pk;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (col + q < N) crow[col + q] = (bf16_t)v[q];
+                    }
+                }
+            }
+        }
+    };
+
     auto run = [&](auto ta_tag) __attribute__((always_inline)) {
         constexpr int TA = decltype(ta_tag)::value;
         constexpr int TA0 = TA < GA ? TA : GA;        // active sub-tiles in group 0 / group 1
@@ -205,49 +251,85 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
             stage(std::integral_constant<int, 0>{}, kt);
             stage(std::integral_constant<int, 1>{}, kt + 1);
         }
-        wait_vmcnt<0>();                           // no load may outlive the workgroup's LDS
-
-        // epilogue: SwiGLU tiles are staged in LDS and written as whole rows by the workgroup,
-        // plain tiles go straight to global memory, 8 bytes (4 columns) per lane
-        const int mrow = lane & 15, cq = (lane >> 4) * 4;
-        if (C::SWIGLU) __builtin_amdgcn_s_barrier();   // every wave's loads have landed
-#pragma unroll
-        for (int i = 0; i < TA; ++i) {
-            const int trow = 16 * (wm + C::WM * i) + mrow;
-            if (!C::SWIGLU && trow >= tile_rows) continue;
-            bf16_t* crow = Cout + (size_t)(row0 + trow) * N;
-            constexpr int JN = C::SWIGLU ? TN16 / 2 : TN16;
-#pragma unroll
-            for (int j = 0; j < JN; ++j) {
-                const int ctile = 16 * (wn * JN + j) + cq;            // column inside the tile
-                float v[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (C::SWIGLU) {
-                        const float gt = acc[i][j][q], up = acc[i][j + JN][q];
-                        v[q] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up;
-                    } else {
-                        v[q] = acc[i][j][q];
-                    }
-                }
-                const uint2 pk = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-                if (C::SWIGLU) {
-                    *reinterpret_cast<uint2*>(lds_raw + trow * kStageRowBytes + ctile * 2) = pk;
-                } else {
-                    const int col = n0 + ctile;
-                    if (col + 3 < N) {
-                        *reinterpret_cast<uint2*>(crow + col) = pk;
-                    } else {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            if (col + q < N) crow[col + q] = (bf16_t)v[q];
-                    }
-                }
-            }
-        }
+        epilogue(acc, ta_tag);
     };
 
-    dispatch_count(ta, run, std::make_integer_sequence<int, TM16 + 1>{});
+    // ---- ping-pong schedule ----------------------------------------------------------------
+    // The two waves that share a SIMD belong to different groups (wm = 0 / 1) and alternate:
+    // while one multiplies a whole k-step out of registers (nothing but matrix instructions),
+    // the other issues its wave-loads and reads its next fragments; a barrier, and they swap.
+    // The matrix pipe of every SIMD always has exactly one wave feeding it, and fragment reads
+    // and load issue never sit between two matrix instructions.  Group 1 runs one phase behind
+    // group 0 (one extra barrier up front, group 0 pays it back at the end).
+    //   phase 2kt  : group 0 reads stage kt            | group 1 multiplies stage kt-1
+    //   phase 2kt+1: group 0 multiplies stage kt       | group 1 reads stage kt
+    // Stage kt+3 is requested in the read phase of stage kt (its slot held stage kt-1, which
+    // group 1 finished reading one phase earlier); before the barrier that ends phase 2kt+1
+    // every wave waits for its share of stage kt+1, so a stage has 4 to 5 phases to land.
+    auto run_pp = [&](auto ta_tag) __attribute__((always_inline)) {
+        static_assert(C::WM == 2 && C::STAGES == 4, "two wave groups, ring of four");
+        constexpr int TA = decltype(ta_tag)::value;
+        constexpr int TAX = TA > 0 ? TA : 1;
+        floatx4 acc[TAX][TN16];
+#pragma unroll
+        for (int i = 0; i < TA; ++i)
+#pragma unroll
+            for (int j = 0; j < TN16; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+        bf16x8 af[TAX], bfr[TN16];
+        const int allow2 = 2 * (a_cnt + C::B_PW);          // two younger stages may be in flight
+
+        // prologue: stages 0..2 requested, stage 0 landed and visible
+#pragma unroll
+        for (int s = 0; s < C::STAGES - 1; ++s)
+#pragma unroll
+            for (int q = 0; q < C::G_MAX; ++q) issue_one(q, s, s);
+        wait_vmcnt_dyn(allow2);
+        __builtin_amdgcn_s_barrier();
+        if (wm == 1) __builtin_amdgcn_s_barrier();         // group 1 sits out phase 0
+
+        int buf = 0;
+        for (int kt = 0; kt < KT; ++kt) {
+            // ---- read phase
+#pragma unroll
+            for (int q = 0; q < C::G_MAX; ++q) issue_one(q, kt + C::STAGES - 1, (buf + 3) & 3);
+            if (TA > 0) {
+                const unsigned char* sa = lds_raw + buf * C::STAGE_BYTES + a_rd;
+                const unsigned char* sb = lds_raw + buf * C::STAGE_BYTES + b_rd;
+#pragma unroll
+                for (int j = 0; j < TN16; ++j)
+                    bfr[j] = *reinterpret_cast<const bf16x8*>(sb + nb(j) * C::ROW_BYTES);
+#pragma unroll
+                for (int i = 0; i < TA; ++i)
+                    af[i] = *reinterpret_cast<const bf16x8*>(sa + i * A_SUB_BYTES);
+            }
+            if (wm == 1) wait_vmcnt_dyn(allow2);           // phase 2kt+1 ends: stage kt+1 landed
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);             // nothing moves across the barriers
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // ---- multiply phase
+            if (!(PROBE & 1)) {
+#pragma unroll
+                for (int i = 0; i < TA; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN16; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j], af[i],
+                                                                            acc[i][j], 0, 0, 0);
+            }
+            if (wm == 0) wait_vmcnt_dyn(allow2);           // phase 2kt+1 ends: stage kt+1 landed
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            buf = (buf + 1) & 3;
+        }
+        if (wm == 0) __builtin_amdgcn_s_barrier();         // group 0 waits out group 1's last phase
+        epilogue(acc, ta_tag);
+    };
+
+    if constexpr (SCHED == 1) dispatch_count(ta, run_pp, std::make_integer_sequence<int, TM16 + 1>{});
+    else dispatch_count(ta, run, std::make_integer_sequence<int, TM16 + 1>{});
 
     if (C::SWIGLU) {
         // cooperative write-out of the staged tile: 16 bytes per lane, whole rows
@@ -277,17 +359,30 @@ hipError_t launch_pipe16(const bf16_t* A, const int32_t* offsets, const bf16_t* 
                          const bf16_t* W1, int n_rows, int E, int N, int K, bf16_t* Cout,
                          hipStream_t s, const int32_t* row_src = nullptr, int topk = 1) {
     static bool attr_set = false;
+    static int sched = 1;
     if (!attr_set) {
+        const char* ev = getenv("SPECMOE_SCHED");      // tuning switch: 0 = lock-step schedule
+        if (ev && ev[0] == '0') sched = 0;
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&grouped_gemm_bf16_pipe16_kernel<C>),
+            reinterpret_cast<const void*>(&grouped_gemm_bf16_pipe16_kernel<C, 0, 0>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&grouped_gemm_bf16_pipe16_kernel<C, 0, 1>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const long long NT = (N + C::BN_OUT - 1) / C::BN_OUT;
     const long long grid = grid_upper_bound(n_rows, E, C::BM, NT);
-    hipLaunchKernelGGL(grouped_gemm_bf16_pipe16_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS),
-                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout, row_src, topk);
+    if (sched == 1)
+        hipLaunchKernelGGL((grouped_gemm_bf16_pipe16_kernel<C, 0, 1>), dim3((unsigned)grid),
+                           dim3(C::THREADS), C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout,
+                           row_src, topk);
+    else
+        hipLaunchKernelGGL((grouped_gemm_bf16_pipe16_kernel<C, 0, 0>), dim3((unsigned)grid),
+                           dim3(C::THREADS), C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout,
+                           row_src, topk);
     return hipGetLastError();
 }
 
