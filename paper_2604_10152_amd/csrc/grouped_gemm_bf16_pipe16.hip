@@ -10,10 +10,12 @@
 // register-only loop with changing operands), and its 16-row granule wastes fewer matrix
 // instructions on the ragged last rows of an expert.
 //
-// Software pipeline inside a stage: the wave's A sub-tiles form two groups.  Group 1's
-// fragments are read while group 0 multiplies; the next stage's B fragments and group 0 are
-// read while group 1 multiplies (the next stage landed one step ago).  B fragments alternate
-// between two register sets, hence the k loop is unrolled by two.
+// Two loop schedules share the set-up and the epilogue.  Default: ping-pong (run_pp): the two
+// waves of a SIMD alternate between multiplying a k-step out of registers and loading /
+// reading the next one.  Alternative (run, SCHED = 0): lock-step software pipeline, where the
+// wave's A sub-tiles form two groups, group 1's fragments are read while group 0 multiplies,
+// the next stage's B fragments and group 0 are read while group 1 multiplies, B fragments
+// alternate between two register sets and the k loop is unrolled by two.
 #include "pipe_common.h"
 
 #include <cstdlib>
