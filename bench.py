@@ -141,6 +141,8 @@ def main():
     ap.add_argument("--mode", choices=["verify", "speculation"], default="verify",
                     help="verify (default): the MoE verify layer, the line the harness reads; "
                          "speculation: per-kernel timings of the draft-routing / sampling rows")
+    ap.add_argument("--no-also", action="store_true",
+                    help="skip the extra 80-token measurement that the default line carries")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a captured HIP graph (one launch per step); the "
                          "gate/up kernel time for the roofline then comes from an eager pass "
@@ -280,7 +282,7 @@ def main():
         "tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else None,
         "roofline": roof,
     }
-    if args.config == 4 and not args.graph:
+    if args.config == 4 and not args.graph and not args.no_also:
         # same weights, the 80-token batch of the Mixtral-shaped configuration (B=16, gamma=4):
         # the memory-bound end of the same layer, reported beside the headline workload
         c2 = synth.CONFIGS[2]
