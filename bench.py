@@ -3,7 +3,9 @@
 
 A step is one pass of the whole hot path over one batch of synthetic input that is already
 resident in HBM: moe_route_topk -> moe_permute -> moe_expert_up_swiglu_gather -> moe_expert_down ->
-moe_combine -> spec_accept.  Prints ONE JSON line (see README / design notes for the fields).
+moe_combine -> spec_accept.  Prints ONE JSON line: tokens/s of the whole step, the roofline
+figure of the gate/up expert GEMM (HIP events around it), and the CPU oracle's rate on a bounded
+sample of the same batch.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..6] [--no-cpu-baseline]
 """

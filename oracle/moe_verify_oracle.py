@@ -18,8 +18,7 @@ What the paper fixes (SpecMoE, arxiv 2604.10152):
   and everything after it, and appends the target's own token at that position.
 * Sec. 3.2 "Expert replacement policy": expert activations are counted during verification.
 
-What the paper leaves open and this file reads as follows (the same readings are listed in
-the design notes of the repository):
+What the paper leaves open and this file reads as follows:
 
 * gate = linear router (+ optional per-expert bias), softmax over all E logits, selection
   of the k largest LOGITS (ties go to the lower expert id, slots ordered by descending

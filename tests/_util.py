@@ -7,8 +7,11 @@ from workloads.metrics import floored_rel_err, max_norm_err  # noqa: F401
 
 # Parity bars.  Integer outputs: bit-exact.  Floating outputs: the benchmark definition's
 # "max relative error" 1e-2 (bf16) / 1e-5 (fp32), measured per output row as
-# max_j |got - want| / max_j |want|  (see the design notes for why the denominator is the
-# row's largest magnitude and not each element's own).
+# max_j |got - want| / max_j |want|.  The denominator is the row's largest magnitude and not
+# each element's own: bf16 rounding of h, y_perm and out leaves an absolute error of a few 1e-3
+# of the row's typical magnitude on every element, so elements near a sign change have
+# unbounded relative error (tests/test_tolerance_model.py shows this on the oracle's own
+# intermediates, no kernel involved).
 TOL = {torch.bfloat16: 1e-2, torch.float32: 1e-5}
 GATE_W_RTOL = 2e-6          # gate weights: fp64 on both sides, one rounding to fp32
 
