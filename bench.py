@@ -262,7 +262,7 @@ def main():
     elif d >= 4096:
         roof["kernel"] = "grouped_gemm_bf16_pipe_kernel<PipeCfg<64,128,64,4,1,2,true>> (gate/up + SwiGLU)"
     else:
-        roof["kernel"] = "grouped_gemm_bf16_kernel<TileCfg<64,128,1,2,true>> (gate/up + SwiGLU)"
+        roof["kernel"] = "grouped_gemm_bf16_kernel<TileCfg<64,256,1,4,true>> (gate/up + SwiGLU)"
     roof["kernel_ms"] = up_ms
     roof["traffic"] = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")

@@ -323,7 +323,7 @@ hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, c
                             : launch_expert_up_bf16_large16(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk);
     if (mid_batch(n_rows, E, d)) return launch_expert_up_bf16_mid(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk);
     if (!use_regstaged() && d >= kLongK) return launch_expert_up_bf16_small(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk);
-    return launch_one<TileCfg<64, 128, 1, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s, row_src, topk);
+    return launch_one<TileCfg<64, 256, 1, 4, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s, row_src, topk);
 }
 
 hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, const bf16_t* wd,
@@ -334,7 +334,7 @@ hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, cons
                             : launch_expert_down_bf16_large16(h, offsets, wd, n_rows, d, f, E, y, s);
     if (mid_batch(n_rows, E, f)) return launch_expert_down_bf16_mid(h, offsets, wd, n_rows, d, f, E, y, s);
     if (!use_regstaged() && f >= kLongK) return launch_expert_down_bf16_small(h, offsets, wd, n_rows, d, f, E, y, s);
-    return launch_one<TileCfg<64, 64, 1, 2, false>>(h, offsets, wd, nullptr, n_rows, E, d, f, y, s);
+    return launch_one<TileCfg<64, 128, 1, 4, false>>(h, offsets, wd, nullptr, n_rows, E, d, f, y, s);
 }
 
 }  // namespace specmoe
