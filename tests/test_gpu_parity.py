@@ -535,3 +535,43 @@ def test_graph_replay_equals_eager():
         assert torch.equal(alen, alen0)
         if not use_alt:
             assert torch.equal(got.view(torch.int16), eager0.view(torch.int16))
+
+
+def test_zero_sizes_and_single_hot_expert():
+    """Degenerate shapes through the whole ABI: no tokens at all (every call is a no-op that leaves
+    its outputs alone, moe_permute still writes offsets), and a batch in which ONE expert takes
+    every row (all other experts empty) in both dtypes."""
+    _say("zero tokens / one expert takes everything")
+    E, d, f, k = 4, 64, 128, 2
+    for dtype in (torch.float32, torch.bfloat16):
+        g = torch.Generator().manual_seed(3)
+        wr = torch.randn(E, d, generator=g).to(dtype).cuda()
+        wg = (torch.randn(E, f, d, generator=g) * 0.1).to(dtype).cuda()
+        wu = (torch.randn(E, f, d, generator=g) * 0.1).to(dtype).cuda()
+        wd = (torch.randn(E, d, f, generator=g) * 0.1).to(dtype).cuda()
+        x0 = torch.zeros((0, d), dtype=dtype, device="cuda")
+        idx0 = torch.zeros((0, k), dtype=I32, device="cuda")
+        w0 = torch.zeros((0, k), dtype=torch.float32, device="cuda")
+        sm.moe_route_topk(x0, wr, None, k, True, idx0, w0)
+        off = torch.full((E + 1,), 9, dtype=I32, device="cuda")
+        sm.moe_permute(x0, idx0, E, x0.new_zeros((0, d)), off, idx0.new_zeros((0,)), idx0.new_zeros((0,)))
+        y0 = torch.zeros((0, d), dtype=dtype, device="cuda")
+        ws = torch.empty((sm.moe_grouped_swiglu_workspace_bytes(0, d, f, E, dtype),), dtype=torch.uint8,
+                         device="cuda")
+        sm.moe_grouped_swiglu(x0, off, wg, wu, wd, y0, ws)
+        out0 = torch.full((0, d), 1.0, dtype=dtype, device="cuda")
+        sm.moe_combine(y0, idx0.new_zeros((0,)), w0, None, out0)
+        torch.cuda.synchronize()
+        assert off.tolist() == [0] * (E + 1)
+        # one expert (id 2) receives every row: bias forces it into slot 0 for every token, the
+        # second slot is spread by the router
+        T = 150
+        x = (torch.randn(T, d, generator=g) / 8).to(dtype).cuda()
+        bias = torch.tensor([0.0, 0.0, 50.0, 0.0], device="cuda")
+        layer = sm.MoEVerifyLayer(T, d, f, E, 1, dtype)
+        out = layer.forward(x, wr, wg, wu, wd, bias)
+        torch.cuda.synchronize()
+        assert layer.expert_offsets.tolist() == [0, 0, 0, T, T]
+        want = orc.moe_layer_brute_force(f64(x), f64(wr), f64(wg), f64(wu), f64(wd), 1, f64(bias), True)
+        assert (layer.topk_idx.cpu().numpy() == 2).all()
+        assert row_rel_err(f64(out), want) <= TOL[dtype]
