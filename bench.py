@@ -273,7 +273,7 @@ def main():
             roof["traffic"] = None
 
     out = {
-        "metric": "moe_verify_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s",
+        "metric": "expert_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
         "data": "synthetic",
