@@ -71,13 +71,6 @@ hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, c
                                  hipStream_t s, const int32_t* row_src = nullptr, int topk = 1);
 hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, const bf16_t* wd,
                                    int n_rows, int d, int f, int E, bf16_t* y, hipStream_t s);
-hipError_t launch_expert_up_bf16_large(const bf16_t* x_perm, const int32_t* offsets,
-                                       const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
-                                       int f, int E, bf16_t* h, hipStream_t s,
-    const int32_t* row_src, int topk);
-hipError_t launch_expert_down_bf16_large(const bf16_t* h, const int32_t* offsets,
-                                         const bf16_t* wd, int n_rows, int d, int f, int E,
-                                         bf16_t* y, hipStream_t s);
 hipError_t launch_expert_up_bf16_large16(const bf16_t* x_perm, const int32_t* offsets,
                                          const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
                                          int f, int E, bf16_t* h, hipStream_t s,

@@ -1,8 +1,9 @@
-// Large-batch expert GEMMs on the gfx950 matrix cores: multi-stage LDS ring filled by
-// direct global->LDS loads, MFMA fragments double-buffered in registers.
-// (SpecMoE Sec. 2.1: only the rows routed to an expert meet its FFN-sized weights;
-// Sec. 2.2: verification brings all B*(gamma+1) tokens at once, so each expert sees hundreds
-// of rows and the contraction is MFMA-bound.)
+// Expert GEMMs for few to a few hundred rows per expert on the gfx950 matrix cores
+// (v_mfma_f32_32x32x16_bf16): multi-stage LDS ring filled by direct global->LDS loads, MFMA
+// fragments double-buffered in registers.
+// (SpecMoE Sec. 2.1: only the rows routed to an expert meet its FFN-sized weights; with a
+// small verification batch - Sec. 2.2 - an expert sees tens of rows and the kernel is bound
+// by streaming its weights from HBM once.)
 //
 // One workgroup = BM rows of one expert x BN weight rows.  Per step of BK contraction
 // elements every wave issues its share of `global_load_lds_dwordx4` instructions: 64 lanes x
@@ -27,12 +28,7 @@ namespace {
 
 using namespace pipe;
 
-// PROBE is 0 in the library.  The tuning harness sets bits to time parts of the pipeline
-// alone: 1 = no matrix instructions, 2 = no global->LDS loads in the loop, 4 = no barrier,
-// 8 = no fragment reads in the loop, 16 = no A loads, 32 = no B loads, 64 = no epilogue,
-// 128 = epilogue without the SwiGLU arithmetic.  Results are meaningless then; only the
-// time counts.
-template <typename C, int PROBE = 0>
+template <typename C>
 __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
     const bf16_t* __restrict__ A,        // [n_rows, K]
     const int32_t* __restrict__ offsets, // [E+1]
@@ -45,8 +41,6 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
     const int NT = (N + C::BN_OUT - 1) / C::BN_OUT;
     TileLoc t;
     if (!locate_tile_even<C::BM>(offsets, E, NT, blockIdx.x, t)) return;
-    long long probe_c0 = 0, probe_w0 = 0;
-    if (PROBE & 256) { probe_c0 = clock64(); probe_w0 = wall_clock64(); }
     const int row0 = t.row0, tile_rows = t.tile_rows;
     const int n0 = t.nt * C::BN_OUT;
     const int nsub = (tile_rows + 31) / 32;
@@ -92,28 +86,19 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
         }
     }
     const int KT = K / C::BK;
-    // Every tile row is K*2 bytes apart, a multiple of the 4 KB period of the L2 channel
-    // interleave for the shapes of interest, so all rows of all tiles at one k offset sit in
-    // the same channel.  Workgroups start together; without a stagger they would sweep the
-    // channels in lockstep.  The k loop is therefore rotated by an amount that depends on the
-    // n-tile only (m-tiles sharing a weight tile stay aligned and still meet in L2).
-    const int kt0 = (int)(((long long)t.nt * C::KROT) % KT);
     // One wave-load of stage kt into ring slot buf.  Loads 0 .. A_PW-1 are this wave's A rows
     // (issued only if they hold real rows), loads A_PW .. A_PW+B_PW-1 its weight rows.
     auto issue_one = [&](int which, int kt, int buf) __attribute__((always_inline)) {
-        if ((PROBE & 2) && kt >= C::STAGES - 1) return;
-        int kq = min(kt, KT - 1) + kt0;                             // clamped: tail re-loads
-        kq = kq >= KT ? kq - KT : kq;
-        const size_t kb = (size_t)kq * C::ROW_BYTES;
+        const size_t kb = (size_t)min(kt, KT - 1) * C::ROW_BYTES;   // clamped: tail re-loads
         const uint32_t sbase = lds_base + (uint32_t)buf * C::STAGE_BYTES + wave * 1024u;
 #pragma unroll
         for (int jj = 0; jj < C::A_PW; ++jj)
-            if (which == jj && jj < a_cnt && !(PROBE & 16))
+            if (which == jj && jj < a_cnt)
                 dma16(a_base + kb, a_off[jj], sbase + jj * C::NWAVES * 1024u);
 #pragma unroll
         for (int jj = 0; jj < C::B_PW; ++jj) {
             const bool up = C::SWIGLU && (jj * C::NWAVES * C::ROWS_PER_DMA >= C::BN / 2);
-            if (which == C::A_PW + jj && !(PROBE & 32))
+            if (which == C::A_PW + jj)
                 dma16((up ? w1 : w0) + kb, b_off[jj], sbase + C::A_BYTES + jj * C::NWAVES * 1024u);
         }
     };
@@ -158,9 +143,8 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
         bf16x8 af[2][TAX], bfr[2][C::TN];
-        auto read_frags = [&](int set, int buf, int kk, bool in_loop) __attribute__((always_inline)) {
+        auto read_frags = [&](int set, int buf, int kk) __attribute__((always_inline)) {
             if (TA == 0) return;
-            if ((PROBE & 8) && in_loop) return;
             const unsigned char* sb = lds_raw + buf * C::STAGE_BYTES;
 #pragma unroll
             for (int j = 0; j < C::TN; ++j)
@@ -171,17 +155,10 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
                                                                32 * C::WM * i * C::ROW_BYTES);
         };
         auto mfma_row = [&](int set, int i) __attribute__((always_inline)) {
-            if (PROBE & 1) {                       // keep the fragment reads alive, no MFMA
-                asm volatile("" :: "v"(af[set][i]));
 #pragma unroll
-                for (int j = 0; j < C::TN; ++j)
-                    asm volatile("" :: "v"(bfr[set][j]));
-                return;
-            }
-#pragma unroll
-                for (int j = 0; j < C::TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i],
-                                                                        acc[i][j], 0, 0, 0);
+            for (int j = 0; j < C::TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i],
+                                                                    acc[i][j], 0, 0, 0);
         };
 
         // prologue: request stages 0 .. STAGES-2, wait for 0 and 1
@@ -189,8 +166,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
         for (int s = 0; s < C::STAGES - 1; ++s) issue_stage(s, s);
         wait_vmcnt_dyn(vm_allow);
         __builtin_amdgcn_s_barrier();
-        read_frags(0, 0, 0, false);
-        if (PROBE & 8) read_frags(1, 0, 1, false);
+        read_frags(0, 0, 0);
 
         int buf = 0;                               // ring slot of stage kt
         for (int kt = 0; kt < KT; ++kt) {
@@ -203,29 +179,25 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
             // the fragment reads next to their use and bunch the loads.
 #pragma unroll
             for (int kk = 0; kk < C::KK; ++kk) {
-                if (kk + 1 < C::KK) read_frags((kk + 1) & 1, buf, kk + 1, true);
-                else read_frags(0, buf_next, 0, true);   // stage kt+1 landed one step ago
+                if (kk + 1 < C::KK) read_frags((kk + 1) & 1, buf, kk + 1);
+                else read_frags(0, buf_next, 0);         // stage kt+1 landed one step ago
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < TAX; ++i) {
                     if (i < TA) mfma_row(kk & 1, i);
                     __builtin_amdgcn_sched_barrier(0);
                     if (kk == 0) {
-                        if (C::SPREAD) {
-                            if (i < C::G_MAX) issue_one(i, kt + C::STAGES - 1, buf_free);
-                            if (i == TAX - 1)
+                        if (i < C::G_MAX) issue_one(i, kt + C::STAGES - 1, buf_free);
+                        if (i == TAX - 1)
 #pragma unroll
-                                for (int q = TAX; q < C::G_MAX; ++q)
-                                    issue_one(q, kt + C::STAGES - 1, buf_free);
-                        } else if (i == 0) {
-                            issue_stage(kt + C::STAGES - 1, buf_free);
-                        }
+                            for (int q = TAX; q < C::G_MAX; ++q)
+                                issue_one(q, kt + C::STAGES - 1, buf_free);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
             wait_vmcnt_dyn(vm_allow);              // own share of stage kt+2 has landed
-            if (!(PROBE & 4)) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_s_barrier();
             buf = buf_next;
         }
         wait_vmcnt<0>();                           // no load may outlive the workgroup's LDS
@@ -238,10 +210,6 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
         //    LDS image of the tile and the workgroup then writes whole 256-byte rows.
         //  - plain tile: 8-byte stores straight to global memory (y is small).
         const int row = lane & 31, chalf = (lane >> 5) * 4;
-        if (PROBE & 64) {
-            if (acc[0][0][0] == 123.456f) Cout[0] = (bf16_t)1.0f;
-            return;
-        }
         if (C::SWIGLU) __builtin_amdgcn_s_barrier();   // every wave's loads have landed: LDS is free
 #pragma unroll
         for (int i = 0; i < TA; ++i) {
@@ -257,7 +225,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
                     float v[4];
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        if (C::SWIGLU && !(PROBE & 128)) {
+                        if (C::SWIGLU) {
                             const float gt = acc[i][j][4 * g + q], up = acc[i][j + JN][4 * g + q];
                             v[q] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up;
                         } else {
@@ -293,12 +261,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
         default: if constexpr (C::TM >= 5) run(std::integral_constant<int, 5>{}); break;
     }
 
-    if ((PROBE & 256) && (blockIdx.x == 8 || blockIdx.x == 801) && threadIdx.x == 0) {
-        const long long dc = clock64() - probe_c0, dw = wall_clock64() - probe_w0;
-        printf("block %d: %lld core clk, %lld ref ticks -> %.0f MHz (if ref = 100 MHz)\n",
-               (int)blockIdx.x, dc, dw, (double)dc / (double)dw * 100.0);
-    }
-    if (C::SWIGLU && !(PROBE & 64)) {
+    if (C::SWIGLU) {
         // cooperative write-out of the staged tile: 16 bytes per lane, whole rows
         static_assert(!C::SWIGLU || (size_t)C::BM * kStageRowBytes <= C::LDS_BYTES, "stage tile");
         __builtin_amdgcn_s_barrier();
@@ -324,14 +287,11 @@ template <typename C>
 hipError_t launch_pipe(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
                        const bf16_t* W1, int n_rows, int E, int N, int K, bf16_t* Cout,
                        hipStream_t s, const int32_t* row_src = nullptr, int topk = 1) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&grouped_gemm_bf16_pipe_kernel<C>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // one-time, thread-safe (C++11 static initialisation): raise the dynamic LDS limit
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(&grouped_gemm_bf16_pipe_kernel<C>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+    if (attr != hipSuccess) return attr;
     const long long NT = (N + C::BN_OUT - 1) / C::BN_OUT;
     const long long grid = grid_upper_bound(n_rows, E, C::BM, NT);
     hipLaunchKernelGGL(grouped_gemm_bf16_pipe_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS),
@@ -340,21 +300,6 @@ hipError_t launch_pipe(const bf16_t* A, const int32_t* offsets, const bf16_t* W0
 }
 
 }  // namespace
-
-hipError_t launch_expert_up_bf16_large(const bf16_t* x_perm, const int32_t* offsets,
-                                       const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
-                                       int f, int E, bf16_t* h, hipStream_t s,
-                                       const int32_t* row_src, int topk) {
-    return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, true>>(x_perm, offsets, wg, wu, n_rows, E, f,
-                                                             d, h, s, row_src, topk);
-}
-
-hipError_t launch_expert_down_bf16_large(const bf16_t* h, const int32_t* offsets,
-                                         const bf16_t* wd, int n_rows, int d, int f, int E,
-                                         bf16_t* y, hipStream_t s) {
-    return launch_pipe<PipeCfg<320, 256, 32, 4, 2, 4, false>>(h, offsets, wd, nullptr, n_rows, E,
-                                                              d, f, y, s);
-}
 
 // Few rows per expert: the weights stream from HBM once and nothing else matters.  64-row
 // tiles, narrow N so that every CU owns a stream, 128-byte rows per step (BK = 64; 64-byte rows

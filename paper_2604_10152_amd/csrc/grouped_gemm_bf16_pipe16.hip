@@ -2,23 +2,18 @@
 // (SpecMoE Sec. 2.1 / 2.2: the rows routed to an expert meet its FFN-sized weights; at
 // verification time each expert sees hundreds of rows, so the contraction is MFMA-bound.)
 //
-// Same data movement as grouped_gemm_bf16_pipe.hip (global->LDS ring of BK = 32 stages, one
-// barrier per step, readiness one step ahead), different matrix instruction: one
-// 16x16x32 MFMA consumes a whole 64-byte tile row per lane, so a stage is ONE k-step.
-// Why this shape: under the chip's power limit the 16x16x32 instruction sustains ~13 % more
-// bf16 flops than 32x32x16 on the same operands (1.97 vs 1.75 PFLOP/s measured in a
-// register-only loop with changing operands), and its 16-row granule wastes fewer matrix
-// instructions on the ragged last rows of an expert.
+// Same data movement as grouped_gemm_bf16_pipe.hip (global->LDS ring of BK = 32 stages),
+// different matrix instruction: one 16x16x32 MFMA consumes a whole 64-byte tile row per lane,
+// so a stage is ONE k-step.
+// Why this shape: under the chip's power limit the 16x16x32 instruction sustains more bf16
+// flops than 32x32x16 on the same operands (2.1 vs 1.8 PFLOP/s measured in a register-only
+// loop with changing operands), and its 16-row granule wastes fewer matrix instructions on
+// the ragged last rows of an expert.
 //
-// Two loop schedules share the set-up and the epilogue.  Default: ping-pong (run_pp): the two
-// waves of a SIMD alternate between multiplying a k-step out of registers and loading /
-// reading the next one.  Alternative (run, SCHED = 0): lock-step software pipeline, where the
-// wave's A sub-tiles form two groups, group 1's fragments are read while group 0 multiplies,
-// the next stage's B fragments and group 0 are read while group 1 multiplies, B fragments
-// alternate between two register sets and the k loop is unrolled by two.
+// Loop schedule: ping-pong.  The two waves of a SIMD alternate between multiplying a k-step
+// out of registers and loading / reading the next one.
 #include "pipe_common.h"
 
-#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -32,7 +27,7 @@ __device__ __forceinline__ void dispatch_count(int n, F& f, std::integer_sequenc
     ((n == Is ? (f(std::integral_constant<int, Is>{}), 0) : 0), ...);
 }
 
-template <typename C, int PROBE = 0, int SCHED = 1>
+template <typename C>
 __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
     const bf16_t* __restrict__ A,        // [n_rows, K]
     const int32_t* __restrict__ offsets, // [E+1]
@@ -43,7 +38,6 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
     static_assert(C::BK == 32, "a stage is exactly one 16x16x32 k-step");
     constexpr int TM16 = C::BM / (16 * C::WM);       // 16-row A sub-tiles per wave
     constexpr int TN16 = C::BN / (16 * C::WN);       // 16-col B sub-tiles per wave
-    constexpr int GA = (TM16 + 1) / 2;               // A sub-tiles per pipeline group
     constexpr int A_SUB_BYTES = 16 * C::WM * C::ROW_BYTES;   // LDS distance of consecutive i
     static_assert(!C::SWIGLU || TN16 % 2 == 0, "gate and up sub-tiles pair up inside a wave");
     static_assert((16 * C::WM) % (C::RPG * C::CHUNKS) == 0, "sub-tile step must keep the swizzle");
@@ -95,7 +89,6 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
     }
     const int KT = K / C::BK;                    // even: the ABI requires K % 64 == 0
     auto issue_one = [&](int which, int kt, int buf) __attribute__((always_inline)) {
-        if ((PROBE & 2) && kt >= C::STAGES - 1) return;
         // the k offset rides in the per-lane offset (one vector add per load); the base
         // pointers stay loop-invariant scalars.  Clamped: the last steps re-load stage KT-1.
         const uint32_t kb = (uint32_t)min(kt, KT - 1) * C::ROW_BYTES;
@@ -124,7 +117,6 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
     };
 
     const int ta = min(TM16, max(0, (nsub - wm + C::WM - 1) / C::WM));   // active A sub-tiles
-    const int vm_allow = (C::STAGES - 3) * (a_cnt + C::B_PW);
 
     // epilogue: SwiGLU tiles are staged in LDS and written as whole rows by the workgroup,
     // plain tiles go straight to global memory, 8 bytes (4 columns) per lane.  acc[i] is the
@@ -169,91 +161,6 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
                 }
             }
         }
-    };
-
-    auto run = [&](auto ta_tag) __attribute__((always_inline)) {
-        constexpr int TA = decltype(ta_tag)::value;
-        constexpr int TA0 = TA < GA ? TA : GA;        // active sub-tiles in group 0 / group 1
-        constexpr int TA1 = TA - TA0;
-        constexpr int TAX = TA > 0 ? TA : 1;
-        floatx4 acc[TAX][TN16];
-#pragma unroll
-        for (int i = 0; i < TA; ++i)
-#pragma unroll
-            for (int j = 0; j < TN16; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
-
-        bf16x8 af[2][GA], bfr[2][TN16];
-        auto read_b = [&](int set, int buf) __attribute__((always_inline)) {
-            if (TA == 0) return;
-            const unsigned char* sb = lds_raw + buf * C::STAGE_BYTES + b_rd;
-#pragma unroll
-            for (int j = 0; j < TN16; ++j)
-                bfr[set][j] = *reinterpret_cast<const bf16x8*>(sb + nb(j) * C::ROW_BYTES);
-        };
-        auto read_a = [&](int grp, int buf) __attribute__((always_inline)) {
-            const unsigned char* sa = lds_raw + buf * C::STAGE_BYTES + a_rd + grp * GA * A_SUB_BYTES;
-#pragma unroll
-            for (int i = 0; i < GA; ++i)
-                if (i < (grp == 0 ? TA0 : TA1))
-                    af[grp][i] = *reinterpret_cast<const bf16x8*>(sa + i * A_SUB_BYTES);
-        };
-        // weights x activations^T: a lane ends up with ONE tile row (lane%16) and four
-        // consecutive output columns 4*(lane/16) + r of the 16x16 sub-tile
-        auto mfma_row = [&](int grp, int i, int bset) __attribute__((always_inline)) {
-            if (PROBE & 1) return;
-#pragma unroll
-            for (int j = 0; j < TN16; ++j)
-                acc[grp * GA + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                    bfr[bset][j], af[grp][i], acc[grp * GA + i][j], 0, 0, 0);
-        };
-
-        // prologue: request stages 0 .. STAGES-2, wait for 0 and 1
-#pragma unroll
-        for (int s = 0; s < C::STAGES - 1; ++s)
-#pragma unroll
-            for (int q = 0; q < C::G_MAX; ++q) issue_one(q, s, s);
-        wait_vmcnt_dyn(vm_allow);
-        __builtin_amdgcn_s_barrier();
-        read_b(0, 0);
-        read_a(0, 0);
-
-        int buf = 0;                               // ring slot of the stage being multiplied
-        auto stage = [&](auto par_tag, int kt) __attribute__((always_inline)) {
-            constexpr int PAR = decltype(par_tag)::value;
-            const int buf_next = (buf + 1 == C::STAGES) ? 0 : buf + 1;
-            const int buf_free = (buf == 0) ? C::STAGES - 1 : buf - 1;   // held stage kt-1
-            read_a(1, buf);
-            // sched_barrier(0) pins the order: fragment reads stay ahead of the matrix
-            // instructions they overlap with, wave-loads go out one per sub-tile row
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < GA; ++i) {
-                if (i < TA0) mfma_row(0, i, PAR);
-                __builtin_amdgcn_sched_barrier(0);
-                if (i < C::G_MAX) issue_one(i, kt + C::STAGES - 1, buf_free);
-                if (i == GA - 1)
-#pragma unroll
-                    for (int q = GA; q < C::G_MAX; ++q) issue_one(q, kt + C::STAGES - 1, buf_free);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            read_b(PAR ^ 1, buf_next);             // stage kt+1 landed one step ago
-            read_a(0, buf_next);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < GA; ++i)
-                if (i < TA1) mfma_row(1, i, PAR);
-            __builtin_amdgcn_sched_barrier(0);
-            wait_vmcnt_dyn(vm_allow);              // own share of stage kt+2 has landed
-            __builtin_amdgcn_s_barrier();
-            buf = buf_next;
-        };
-        for (int kt = 0; kt < KT; kt += 2) {
-            stage(std::integral_constant<int, 0>{}, kt);
-            stage(std::integral_constant<int, 1>{}, kt + 1);
-        }
-        epilogue(acc, ta_tag);
     };
 
     // ---- ping-pong schedule ----------------------------------------------------------------
@@ -312,14 +219,12 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             // ---- multiply phase
-            if (!(PROBE & 1)) {
 #pragma unroll
-                for (int i = 0; i < TA; ++i)
+            for (int i = 0; i < TA; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN16; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j], af[i],
-                                                                            acc[i][j], 0, 0, 0);
-            }
+                for (int j = 0; j < TN16; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j], af[i], acc[i][j],
+                                                                        0, 0, 0);
             if (wm == 0) wait_vmcnt_dyn(allow2);           // phase 2kt+1 ends: stage kt+1 landed
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_barrier();
@@ -330,8 +235,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
         epilogue(acc, ta_tag);
     };
 
-    if constexpr (SCHED == 1) dispatch_count(ta, run_pp, std::make_integer_sequence<int, TM16 + 1>{});
-    else dispatch_count(ta, run, std::make_integer_sequence<int, TM16 + 1>{});
+    dispatch_count(ta, run_pp, std::make_integer_sequence<int, TM16 + 1>{});
 
     if (C::SWIGLU) {
         // cooperative write-out of the staged tile: 16 bytes per lane, whole rows
@@ -360,31 +264,15 @@ template <typename C>
 hipError_t launch_pipe16(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
                          const bf16_t* W1, int n_rows, int E, int N, int K, bf16_t* Cout,
                          hipStream_t s, const int32_t* row_src = nullptr, int topk = 1) {
-    static bool attr_set = false;
-    static int sched = 1;
-    if (!attr_set) {
-        const char* ev = getenv("SPECMOE_SCHED");      // tuning switch: 0 = lock-step schedule
-        if (ev && ev[0] == '0') sched = 0;
-        hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&grouped_gemm_bf16_pipe16_kernel<C, 0, 0>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&grouped_gemm_bf16_pipe16_kernel<C, 0, 1>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // one-time, thread-safe (C++11 static initialisation): raise the dynamic LDS limit
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(&grouped_gemm_bf16_pipe16_kernel<C>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+    if (attr != hipSuccess) return attr;
     const long long NT = (N + C::BN_OUT - 1) / C::BN_OUT;
     const long long grid = grid_upper_bound(n_rows, E, C::BM, NT);
-    if (sched == 1)
-        hipLaunchKernelGGL((grouped_gemm_bf16_pipe16_kernel<C, 0, 1>), dim3((unsigned)grid),
-                           dim3(C::THREADS), C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout,
-                           row_src, topk);
-    else
-        hipLaunchKernelGGL((grouped_gemm_bf16_pipe16_kernel<C, 0, 0>), dim3((unsigned)grid),
-                           dim3(C::THREADS), C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout,
-                           row_src, topk);
+    hipLaunchKernelGGL(grouped_gemm_bf16_pipe16_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS),
+                       C::LDS_BYTES, s, A, offsets, W0, W1, E, N, K, Cout, row_src, topk);
     return hipGetLastError();
 }
 

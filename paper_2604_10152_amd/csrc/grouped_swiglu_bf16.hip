@@ -1,4 +1,5 @@
-// Experts in bf16 mode: grouped SwiGLU FFN on the gfx950 matrix cores.
+// Experts in bf16 mode: dispatch of the two expert contractions to a kernel family by shape,
+// and the register-staged kernel used for short contractions.
 // (SpecMoE Sec. 2.1: every expert is an FFN-sized block; only the rows routed to an expert
 // are multiplied with its weights.  At verification time all B*(gamma+1) tokens arrive at
 // once - Sec. 2.2 - which is what makes this a dense contraction worth the MFMA units.)
@@ -6,21 +7,22 @@
 // Two launches: (1) h = silu(x Wg^T) * (x Wu^T) with gate and up columns of one f-range in
 // the same tile so the SwiGLU epilogue happens on the accumulators; (2) y = h Wd^T.
 // Both are "NT" GEMMs: A rows and W rows are contiguous along the contraction axis, which is
-// the layout v_mfma_f32_32x32x16_bf16 wants (each lane feeds 8 consecutive k of one row).
+// the layout the bf16 matrix instructions want (each lane feeds 8 consecutive k of one row).
 //
-// Tiling: a workgroup owns BM rows of ONE expert x BN weight rows, BK = 64 per step, tiles
-// staged through LDS (double buffered, 16-byte chunks XOR-swizzled by row so that both the
-// 128-byte-row stores and the MFMA fragment reads are bank-conflict free).  m-tiles never
-// straddle experts; the tile -> (expert, n-tile, m-tile) map is computed on the device from
-// expert_offsets (no host read-back).  Workgroup ids are dealt round-robin to the 8 XCDs by
-// the hardware, so the map sends consecutive logical tiles - the m-tiles that share one
-// weight tile, then the next n-tile of the same expert - to the same XCD and its L2.
+// Register-staged kernel (grouped_gemm_bf16_kernel, v_mfma_f32_32x32x16_bf16): a workgroup
+// owns BM = 64 rows of ONE expert x BN weight rows, BK = 64 per step; the next step's tile is
+// loaded into registers while the current one is multiplied, then stored to the other LDS
+// buffer (16-byte chunks XOR-swizzled by row so that both the 128-byte-row stores and the
+// MFMA fragment reads are bank-conflict free).  It serves short contraction axes (fine-grained
+// experts), where a tile lives for a few dozen steps and several co-resident workgroups per CU
+// hide each other's prologue and epilogue.  m-tiles never straddle experts; the tile ->
+// (expert, n-tile, m-tile) map is computed on the device from expert_offsets (no host
+// read-back), consecutive logical tiles go to the same XCD and its L2 (tile_map.h).
 // 32-row MFMA sub-tiles beyond the expert's last row are skipped (wave-uniform), and waves
 // take sub-tiles interleaved so that a partial tile stays balanced across the SIMDs.
 #include "common.h"
 #include "tile_map.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace specmoe {
@@ -254,14 +256,11 @@ template <typename C>
 hipError_t launch_one(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
                       const bf16_t* W1, int n_rows, int E, int N, int K, bf16_t* Cout,
                       hipStream_t s, const int32_t* row_src = nullptr, int topk = 1) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&grouped_gemm_bf16_kernel<C>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // one-time, thread-safe (C++11 static initialisation): raise the dynamic LDS limit
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(&grouped_gemm_bf16_kernel<C>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+    if (attr != hipSuccess) return attr;
     const long long NT = (N + C::BN_OUT - 1) / C::BN_OUT;
     const long long max_mt = n_rows / C::BM + E;     // sum_e ceil(M_e/BM) <= floor(P/BM) + E
     long long grid = max_mt * NT;
@@ -273,24 +272,14 @@ hipError_t launch_one(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
 
 }  // namespace
 
-// tuning switch (environment): SPECMOE_TIER=large|mid|small forces one kernel family
-static inline int forced_tier() {
-    static int v = -2;
-    if (v == -2) {
-        const char* e = getenv("SPECMOE_TIER");
-        v = !e ? -1 : (e[0] == 'l' ? 2 : (e[0] == 'm' ? 1 : (e[0] == 's' ? 0 : -1)));
-    }
-    return v;
-}
-// rows per expert (average) from which a tier applies: >= 192 large (MFMA-bound, 320-row
-// tiles), >= 48 with a long contraction mid (128-row tiles), below that small (64-row tiles)
+// Rows per expert (average) from which a kernel family applies: >= 192 large (MFMA-bound,
+// up to 320-row tiles), >= 48 with a long contraction mid (128-row tiles), below that small
+// (64-row tiles).
 constexpr int g_large_rows = 192, g_mid_rows = 48;
 static inline bool large_batch(int n_rows, int E) {
-    if (forced_tier() >= 0) return forced_tier() == 2;
     return (long long)n_rows >= (long long)g_large_rows * E;
 }
 static inline bool mid_batch(int n_rows, int E, int K) {
-    if (forced_tier() >= 0) return forced_tier() == 1;
     return K >= 4096 && (long long)n_rows >= (long long)g_mid_rows * E;
 }
 // Few rows per expert, two kernels: with a long contraction axis the deep global->LDS ring wins
@@ -298,18 +287,6 @@ static inline bool mid_batch(int n_rows, int E, int K) {
 // for a few dozen steps only and three co-resident register-staged workgroups per CU hide the
 // prologue / epilogue of each other better (360 vs 490 us at the 64-expert shape).
 constexpr int kLongK = 4096;
-// tuning switch (environment): SPECMOE_MFMA32=1 selects the 32x32x16 large-batch kernels
-static inline bool use_mfma32() {
-    static int v = -1;
-    if (v < 0) { const char* e = getenv("SPECMOE_MFMA32"); v = (e && e[0] == '1') ? 1 : 0; }
-    return v == 1;
-}
-// tuning switch (environment): SPECMOE_REGSTAGED=1 selects the register-staged small-batch kernels
-static inline bool use_regstaged() {
-    static int v = -1;
-    if (v < 0) { const char* e = getenv("SPECMOE_REGSTAGED"); v = (e && e[0] == '1') ? 1 : 0; }
-    return v == 1;
-}
 
 // Large batches: up to 320-row tiles, 8 wavefronts, MFMA-bound.  Fewer rows per expert: the
 // weights stream once from HBM and narrow tiles give every CU its own stream (measured at 16
@@ -319,10 +296,14 @@ hipError_t launch_expert_up_bf16(const bf16_t* x_perm, const int32_t* offsets, c
                                  hipStream_t s, const int32_t* row_src, int topk) {
     if (n_rows == 0) return hipSuccess;
     if (large_batch(n_rows, E))
-        return use_mfma32() ? launch_expert_up_bf16_large(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk)
-                            : launch_expert_up_bf16_large16(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk);
-    if (mid_batch(n_rows, E, d)) return launch_expert_up_bf16_mid(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk);
-    if (!use_regstaged() && d >= kLongK) return launch_expert_up_bf16_small(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src, topk);
+        return launch_expert_up_bf16_large16(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s,
+                                             row_src, topk);
+    if (mid_batch(n_rows, E, d))
+        return launch_expert_up_bf16_mid(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src,
+                                         topk);
+    if (d >= kLongK)
+        return launch_expert_up_bf16_small(x_perm, offsets, wg, wu, n_rows, d, f, E, h, s, row_src,
+                                           topk);
     return launch_one<TileCfg<64, 256, 1, 4, true>>(x_perm, offsets, wg, wu, n_rows, E, f, d, h, s, row_src, topk);
 }
 
@@ -330,10 +311,10 @@ hipError_t launch_expert_down_bf16(const bf16_t* h, const int32_t* offsets, cons
                                    int n_rows, int d, int f, int E, bf16_t* y, hipStream_t s) {
     if (n_rows == 0) return hipSuccess;
     if (large_batch(n_rows, E))
-        return use_mfma32() ? launch_expert_down_bf16_large(h, offsets, wd, n_rows, d, f, E, y, s)
-                            : launch_expert_down_bf16_large16(h, offsets, wd, n_rows, d, f, E, y, s);
-    if (mid_batch(n_rows, E, f)) return launch_expert_down_bf16_mid(h, offsets, wd, n_rows, d, f, E, y, s);
-    if (!use_regstaged() && f >= kLongK) return launch_expert_down_bf16_small(h, offsets, wd, n_rows, d, f, E, y, s);
+        return launch_expert_down_bf16_large16(h, offsets, wd, n_rows, d, f, E, y, s);
+    if (mid_batch(n_rows, E, f))
+        return launch_expert_down_bf16_mid(h, offsets, wd, n_rows, d, f, E, y, s);
+    if (f >= kLongK) return launch_expert_down_bf16_small(h, offsets, wd, n_rows, d, f, E, y, s);
     return launch_one<TileCfg<64, 128, 1, 4, false>>(h, offsets, wd, nullptr, n_rows, E, d, f, y, s);
 }
 

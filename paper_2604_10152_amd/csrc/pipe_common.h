@@ -7,10 +7,8 @@
 namespace specmoe {
 namespace pipe {
 
-template <int BM_, int BN_, int BK_, int STAGES_, int WM_, int WN_, bool SWIGLU_, int KROT_ = 0>
+template <int BM_, int BN_, int BK_, int STAGES_, int WM_, int WN_, bool SWIGLU_>
 struct PipeCfg {
-    static constexpr int KROT = KROT_ % 1000;        // k-loop rotation per n-tile, in steps
-    static constexpr bool SPREAD = KROT_ < 1000;     // tuning switch: spread the wave-loads
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_, WM = WM_, WN = WN_;
     static constexpr bool SWIGLU = SWIGLU_;
     static constexpr int NWAVES = WM * WN, THREADS = NWAVES * kWave;
@@ -49,10 +47,11 @@ __device__ __forceinline__ int swz(int r, int c) {
 // so that the 8-byte accumulator stores of 32 consecutive rows spread over the banks).
 constexpr int kStageRowBytes = 128 * 2 + 16;
 
-// 64 lanes x 16 bytes: global (uniform base + per-lane byte offset) -> LDS [lds_addr, +1024)
+// 64 lanes x 16 bytes: global (uniform base + per-lane byte offset) -> LDS [lds_addr, +1024).
+// The LDS destination travels in m0, which the statement overwrites (declared as a clobber).
 __device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
+                 :: "v"(voff), "s"(gbase), "s"(lds_addr) : "memory", "m0");
 }
 // tells the compiler that a pointer is the same in every lane (it then lives in scalar registers,
 // which the "s" operand of dma16 requires)
