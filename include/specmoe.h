@@ -90,6 +90,21 @@ int moe_grouped_swiglu(const void* x_perm, const int32_t* expert_offsets,
                        int n_rows, int d_model, int d_ff, int E, int dtype,
                        void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
 
+/* moe_grouped_swiglu for callers that cannot allocate device memory or size a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * intermediate h lives in a file-scope device array of the library instead of a caller
+ * workspace.  Same kernels and the same results as moe_grouped_swiglu.  The call allocates
+ * nothing; n_rows * d_ff * sizeof(element) must not exceed SPECMOE_STATIC_SCRATCH_BYTES
+ * (SPECMOE_ERR_WORKSPACE otherwise, nothing launched).  Every GPU the library runs on holds
+ * its own copy of the array until the process ends.  All calls on one GPU share it, so calls
+ * that overlap in time on one GPU (different streams or threads) race on h; rows [0, n_rows)
+ * of h are fully overwritten by every call, nothing has to start at zero. */
+#define SPECMOE_STATIC_SCRATCH_BYTES (16u << 20)
+int moe_grouped_swiglu_static(const void* x_perm, const int32_t* expert_offsets,
+                              const void* w_gate, const void* w_up, const void* w_down,
+                              int n_rows, int d_model, int d_ff, int E, int dtype,
+                              void* y_perm, void* stream);
+
 /* The two halves of moe_grouped_swiglu as separate calls (same definitions, same kernels):
  *   moe_expert_up_swiglu:  h[r] = silu(x_perm[r] . w_gate[e]^T) * (x_perm[r] . w_up[e]^T)
  *   moe_expert_down:       y_perm[r] = h[r] . w_down[e]^T

@@ -17,6 +17,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "moe_route_topk", "moe_permute", "moe_grouped_swiglu_workspace_bytes", "moe_grouped_swiglu",
+    "moe_grouped_swiglu_static",
     "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down", "moe_combine", "spec_accept", "moe_hot_experts", "moe_rmsnorm", "specmoe_status_string", "specmoe_abi_version",
     "moe_affinity_table_workspace_bytes", "moe_affinity_table", "moe_nearest_draft_expert",
     "moe_route_topk_draft", "spec_accept_sample", "spec_greedy_tokens", "moe_active_expert_bytes",
@@ -54,6 +55,7 @@ def load_library(build_if_missing: bool = True):
     lib.moe_grouped_swiglu_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.moe_grouped_swiglu_workspace_bytes.restype = sz
     lib.moe_grouped_swiglu.argtypes = [vp, ip, vp, vp, vp, i, i, i, i, i, vp, vp, sz, vp]
+    lib.moe_grouped_swiglu_static.argtypes = [vp, ip, vp, vp, vp, i, i, i, i, i, vp, vp]
     lib.moe_expert_up_swiglu.argtypes = [vp, ip, vp, vp, i, i, i, i, i, vp, vp]
     lib.moe_expert_up_swiglu_gather.argtypes = [vp, ip, i, i, ip, vp, vp, i, i, i, i, i, vp, vp]
     lib.moe_expert_down.argtypes = [vp, ip, vp, i, i, i, i, i, vp, vp]
@@ -73,6 +75,7 @@ def load_library(build_if_missing: bool = True):
     lib.specmoe_status_string.restype = ctypes.c_char_p
     lib.specmoe_abi_version.restype = i
     for name in ("moe_route_topk", "moe_permute", "moe_grouped_swiglu", "moe_combine",
+                 "moe_grouped_swiglu_static",
                  "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down",
                  "moe_hot_experts", "moe_affinity_table", "moe_nearest_draft_expert",
                  "moe_route_topk_draft", "spec_accept_sample", "spec_greedy_tokens",
@@ -155,6 +158,16 @@ def moe_grouped_swiglu(x_perm, expert_offsets, w_gate, w_up, w_down, y_perm, wor
         _ptr(w_down, x_perm.dtype, "w_down"), n_rows, d, f, E, _dtype_code(x_perm),
         _ptr(y_perm, x_perm.dtype, "y_perm"), _ptr(workspace, torch.uint8, "workspace"),
         workspace.numel(), _stream(stream)), "moe_grouped_swiglu")
+
+
+def moe_grouped_swiglu_static(x_perm, expert_offsets, w_gate, w_up, w_down, y_perm, stream=None):
+    n_rows, d = x_perm.shape
+    E, f, _ = w_gate.shape
+    _check(load_library().moe_grouped_swiglu_static(
+        _ptr(x_perm, name="x_perm"), _ptr(expert_offsets, torch.int32, "expert_offsets"),
+        _ptr(w_gate, x_perm.dtype, "w_gate"), _ptr(w_up, x_perm.dtype, "w_up"),
+        _ptr(w_down, x_perm.dtype, "w_down"), n_rows, d, f, E, _dtype_code(x_perm),
+        _ptr(y_perm, x_perm.dtype, "y_perm"), _stream(stream)), "moe_grouped_swiglu_static")
 
 
 def moe_expert_up_swiglu(x_perm, expert_offsets, w_gate, w_up, h, stream=None):

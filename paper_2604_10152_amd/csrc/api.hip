@@ -5,6 +5,8 @@
 
 #include <limits.h>
 
+#include <mutex>
+
 using namespace specmoe;
 
 namespace {
@@ -131,6 +133,54 @@ int moe_grouped_swiglu(const void* x_perm, const int32_t* expert_offsets, const 
                            y_perm, stream);
 }
 
+// Scratch of moe_grouped_swiglu_static: one copy per GPU, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[SPECMOE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU (0 = unknown)
+
+// Device address of the scratch array on the current GPU.  The array's name is only a
+// host-side handle; the address comes from hipGetSymbolAddress, once per device.
+int scratch_address(void** out) {
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices)
+        return SPECMOE_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+            return SPECMOE_ERR_DEVICE;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return SPECMOE_OK;
+}
+}  // namespace
+
+int moe_grouped_swiglu_static(const void* x_perm, const int32_t* expert_offsets,
+                              const void* w_gate, const void* w_up, const void* w_down,
+                              int n_rows, int d_model, int d_ff, int E, int dtype, void* y_perm,
+                              void* stream) {
+    int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
+    if (st != SPECMOE_OK) return st;
+    if (n_rows == 0) return SPECMOE_OK;
+    if (!x_perm || !expert_offsets || !w_gate || !w_up || !w_down || !y_perm)
+        return SPECMOE_ERR_NULL;
+    if ((unsigned long long)n_rows * (unsigned long long)d_ff * esize(dtype) >
+        (unsigned long long)SPECMOE_STATIC_SCRATCH_BYTES)
+        return SPECMOE_ERR_WORKSPACE;
+    void* h = nullptr;
+    st = scratch_address(&h);
+    if (st != SPECMOE_OK) return st;
+    st = moe_expert_up_swiglu(x_perm, expert_offsets, w_gate, w_up, n_rows, d_model, d_ff, E,
+                              dtype, h, stream);
+    if (st != SPECMOE_OK) return st;
+    return moe_expert_down(h, expert_offsets, w_down, n_rows, d_model, d_ff, E, dtype, y_perm,
+                           stream);
+}
+
 int moe_combine(const void* y_perm, const int32_t* row_of, const float* topk_w,
                 const void* residual, int T, int d_model, int k, int dtype, void* out,
                 void* stream) {
@@ -254,6 +304,6 @@ const char* specmoe_status_string(int status) {
     }
 }
 
-int specmoe_abi_version(void) { return 4; }
+int specmoe_abi_version(void) { return 5; }
 
 }  // extern "C"

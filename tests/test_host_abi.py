@@ -29,7 +29,7 @@ def test_header_and_library_agree(lib):
     assert set(declared) == set(binding.EXPORTED_SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.specmoe_abi_version() == 4
+    assert lib.specmoe_abi_version() == 5
 
 
 def test_status_strings(lib):
@@ -49,6 +49,16 @@ def test_workspace_query(lib):
 
 P = ctypes.c_void_p(0x1000)   # never dereferenced: validation fails first in every call below
 N = None
+
+
+def test_static_scratch_validation(lib):
+    f = lib.moe_grouped_swiglu_static
+    assert f(P, P, P, P, P, 8, 64, 64, 2, 7, P, N) == 3                  # dtype
+    assert f(P, P, P, P, P, 8, 64, 60, 2, 1, P, N) == 2                  # d_ff % 64 in bf16
+    assert f(N, P, P, P, P, 8, 64, 64, 2, 1, P, N) == 1                  # NULL
+    assert f(P, P, P, P, P, 8193, 64, 1024, 2, 1, P, N) == 4             # beyond the 16 MiB scratch
+    assert f(P, P, P, P, P, 4097, 64, 1024, 2, 0, P, N) == 4             # same, fp32
+    assert f(P, P, P, P, P, 0, 64, 64, 2, 1, P, N) == 0                  # nothing to do
 
 
 def test_route_validation(lib):
