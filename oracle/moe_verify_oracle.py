@@ -281,9 +281,14 @@ def decoder_stack(x, layers, k, renorm=True, eps=1e-5):
 # by-products used by the paper's policy and reporting
 # --------------------------------------------------------------------------------------
 def skewness(counts):
-    """Share of routed pairs that go to the hottest quarter of the experts (Table I caption)."""
+    """Share of routed pairs that go to the hottest quarter of the experts (Table I caption).
+
+    The quarter is ceil(E / 4) experts: Sec. 6.1 states that the value lies between 0.25 and 1,
+    which for E not divisible by 4 holds only if the quarter is rounded up (uniform counts then
+    give ceil(E/4)/E >= 0.25).
+    """
     counts = np.sort(np.asarray(counts, dtype=F64))[::-1]
-    top = max(1, int(round(len(counts) * 0.25)))
+    top = -(-len(counts) // 4)
     total = counts.sum()
     return float(counts[:top].sum() / total) if total > 0 else 0.0
 

@@ -27,6 +27,39 @@ def row_rel_err(got, want):
     return float((num / np.maximum(den, floor)).max())
 
 
+# Second, tighter bar (catches a systematic bias that the max-norm bar would let through):
+# per row, rms(got - want) / rms(want).  Three independent bf16 roundings (h, y_perm, out) of
+# relative size <= 2^-9 each give about 2^-9 * sqrt(3) / sqrt(3) ~ 2e-3; a 1 % bias gives 1e-2.
+RMS_TOL = {torch.bfloat16: 4e-3, torch.float32: 2e-6}
+# fp32 mode has no 16-bit rounding anywhere, so the element-wise measure with the denominator
+# floored at 1e-3 of the tensor's largest magnitude is asserted as well.
+F32_FLOORED_TOL = 1e-5
+
+
+def row_rms_err(got, want):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    if want.size == 0:
+        return 0.0
+    num = np.sqrt(((got - want) ** 2).mean(axis=1))
+    den = np.sqrt((want ** 2).mean(axis=1))
+    floor = np.sqrt((want ** 2).mean()) * 1e-6 + 1e-300
+    return float((num / np.maximum(den, floor)).max())
+
+
+def check_float(got, want, dtype, label=""):
+    """All floating-point bars of one output tensor; prints the measures, returns the max-norm one."""
+    e_max, e_rms = row_rel_err(got, want), row_rms_err(got, want)
+    e_flo = floored_rel_err(got, want)
+    print(f"   {label}: row max-norm {e_max:.3e}  row rms {e_rms:.3e}  floored element-wise "
+          f"{e_flo:.3e}", flush=True)
+    assert e_max <= TOL[dtype], (label, "max-norm", e_max)
+    assert e_rms <= RMS_TOL[dtype], (label, "rms", e_rms)
+    if dtype == torch.float32:
+        assert e_flo <= F32_FLOORED_TOL, (label, "floored element-wise", e_flo)
+    return e_max
+
+
 class LazyF64:
     """Per-expert fp64 view of an [E, ...] tensor; widened only when an expert is used."""
 

@@ -339,6 +339,49 @@ def test_decoder_stack_is_prenorm_residual():
     assert np.allclose(orc.decoder_stack(p["x"], zero, 2), p["x"])
 
 
+def test_decoder_stack_with_identical_experts_is_a_dense_prenorm_mlp_stack():
+    """If all experts of a layer share their weights, renormalised gates make the MoE block the
+    plain FFN, so the stack is h <- h + Wd(silu(Wg n) * (Wu n)), n = rms_norm(h) * gain: written
+    here with torch's own rms_norm / silu / linear in fp64, layer weights and gains all different."""
+    F = torch.nn.functional
+    g = torch.Generator().manual_seed(77)
+    T, d, f, E, n_layers, eps = 7, 12, 20, 5, 3, 1e-5
+    x = torch.randn(T, d, generator=g, dtype=torch.float64)
+    layers, h = [], x.clone()
+    for _ in range(n_layers):
+        wg = torch.randn(f, d, generator=g, dtype=torch.float64) * 0.4
+        wu = torch.randn(f, d, generator=g, dtype=torch.float64) * 0.4
+        wd = torch.randn(d, f, generator=g, dtype=torch.float64) * 0.4
+        gain = 1.0 + 0.3 * torch.randn(d, generator=g, dtype=torch.float64)
+        wr = torch.randn(E, d, generator=g, dtype=torch.float64)
+        layers.append(dict(gain=gain.numpy(), w_router=wr.numpy(), bias=None,
+                           w_gate=np.stack([wg.numpy()] * E), w_up=np.stack([wu.numpy()] * E),
+                           w_down=np.stack([wd.numpy()] * E)))
+        n = F.rms_norm(h, (d,), weight=gain, eps=eps)
+        h = h + F.linear(F.silu(F.linear(n, wg)) * F.linear(n, wu), wd)
+    got = orc.decoder_stack(x.numpy(), layers, 2, True, eps)
+    np.testing.assert_allclose(got, h.numpy(), rtol=1e-11, atol=1e-12)
+    # the residual and the per-layer normalisation both matter: dropping either changes the result
+    no_res = x.clone()
+    for L in layers:
+        n = F.rms_norm(no_res, (d,), weight=torch.from_numpy(L["gain"]), eps=eps)
+        no_res = F.linear(F.silu(F.linear(n, torch.from_numpy(L["w_gate"][0]))) *
+                          F.linear(n, torch.from_numpy(L["w_up"][0])), torch.from_numpy(L["w_down"][0]))
+    assert np.abs(got - no_res.numpy()).max() > 1e-2
+
+
+def test_skewness_quarter_is_rounded_up():
+    """Hand values for expert counts not divisible by 4 (quarter = ceil(E/4) experts), and the
+    lower bound 0.25 the paper states, for every E."""
+    assert abs(orc.skewness(np.array([5, 4, 3, 2, 1, 0])) - 9 / 15) < 1e-15          # E = 6: 2 experts
+    assert abs(orc.skewness(np.array([1, 9, 2, 8, 3, 7, 4, 6, 5, 0])) - 24 / 45) < 1e-15   # E = 10: 3
+    assert abs(orc.skewness(np.array([2, 7, 1, 5, 3])) - 12 / 18) < 1e-15            # E = 5: 2
+    assert orc.skewness(np.array([3.0])) == 1.0
+    for E in range(1, 21):
+        s = orc.skewness(np.full(E, 7))
+        assert 0.25 <= s <= 1.0 and abs(s - (-(-E // 4)) / E) < 1e-15
+
+
 def test_skewness_and_hot_experts():
     """Table I caption: skewness = share of pairs on the hottest quarter of experts, in [0.25, 1]."""
     assert orc.skewness(np.full(8, 10)) == 0.25
