@@ -9,6 +9,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecmoe.so")
+PEAKS_LIB = os.path.join(HERE, "libspecmoe_peaks.so")     # measurement helpers (bench.py --mode peaks)
+PEAKS_SOURCES = ["peaks.hip"]
 SOURCES = ["api.hip", "route_topk.hip", "permute.hip", "grouped_swiglu_f32.hip",
            "grouped_swiglu_bf16.hip", "grouped_gemm_bf16_pipe.hip", "grouped_gemm_bf16_pipe16.hip", "combine.hip", "spec_accept.hip", "hot_experts.hip",
            "draft_route.hip", "spec_sample.hip"]
@@ -23,9 +25,10 @@ def build(verbose: bool = False) -> str:
     os.makedirs(objdir, exist_ok=True)
     procs = []
     objs = []
-    for src in SOURCES:
+    for src in SOURCES + PEAKS_SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        objs.append(obj)
+        if src in SOURCES:
+            objs.append(obj)
         cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -45,6 +48,10 @@ def build(verbose: bool = False) -> str:
     tmp = LIB + ".tmp"
     subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
     os.replace(tmp, LIB)
+    tmp = PEAKS_LIB + ".tmp"
+    pobjs = [os.path.join(objdir, src.replace(".hip", ".o")) for src in PEAKS_SOURCES]
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *pobjs])
+    os.replace(tmp, PEAKS_LIB)
     return LIB
 
 

@@ -29,11 +29,15 @@ def row_rel_err(got, want):
 
 # Second, tighter bar (catches a systematic bias that the max-norm bar would let through):
 # per row, rms(got - want) / rms(want).  Three independent bf16 roundings (h, y_perm, out) of
-# relative size <= 2^-9 each give about 2^-9 * sqrt(3) / sqrt(3) ~ 2e-3; a 1 % bias gives 1e-2.
-RMS_TOL = {torch.bfloat16: 4e-3, torch.float32: 2e-6}
+# relative size <= 2^-9 each leave 2e-3 to 3.5e-3 (tests/test_tolerance_model.py, ideal model);
+# a 1 % bias gives 1e-2.
+RMS_TOL = {torch.bfloat16: 5e-3, torch.float32: 2e-6}
 # fp32 mode has no 16-bit rounding anywhere, so the element-wise measure with the denominator
-# floored at 1e-3 of the tensor's largest magnitude is asserted as well.
-F32_FLOORED_TOL = 1e-5
+# floored at 1e-3 of the tensor's largest magnitude is printed and asserted as well.  Its bar is
+# 1e-3, not 1e-5: fp32 running sums leave an absolute error of a few 1e-7 of a row's typical
+# magnitude, which is a few 1e-4 of an element 1000 times smaller than the maximum
+# (tests/test_tolerance_model.py reproduces this with numpy float32 matmuls, no kernel).
+F32_FLOORED_TOL = 1e-3
 
 
 def row_rms_err(got, want):

@@ -41,9 +41,50 @@ def test_mandatory_bf16_roundings_fit_row_norm_bar_but_not_elementwise_floor():
         got[t] = _bf16(acc)                                          # rounding point 3
     row = _row_err(got, want)
     elem = floored_rel_err(got, want, floor_frac=1e-3)
-    print(f"ideal bf16 pipeline: per-row err {row:.2e}, floored element-wise err {elem:.2e}")
+    rms = float((np.sqrt(((got - want) ** 2).mean(axis=1)) / np.sqrt((want ** 2).mean(axis=1))).max())
+    print(f"ideal bf16 pipeline: per-row err {row:.2e}, per-row rms err {rms:.2e}, "
+          f"floored element-wise err {elem:.2e}")
+    # second bar of the GPU tests: per-row rms error <= 5e-3.  Unbiased rounding stays below it
+    # with margin; a 1 % systematic error (which the max-norm bar alone would pass) does not.
+    assert rms < 4e-3, rms
+    biased = got * 1.01
+    assert float((np.sqrt(((biased - want) ** 2).mean(axis=1)) /
+                  np.sqrt((want ** 2).mean(axis=1))).min()) > 5e-3
     # the per-row max-norm error of an ideal implementation sits below the 1e-2 bar ...
     assert row < 1e-2, row
     # ... while element-wise relative error with a floor at 1e-3 of the tensor maximum is
     # already beyond 1e-2 for it: small elements inherit the absolute rounding error of h.
     assert elem > 1e-2, elem
+
+
+def test_fp32_arithmetic_meets_row_bar_but_not_the_floored_elementwise_one():
+    """fp32 mode on the cfg-1 shape, no kernel involved: the same definition evaluated with
+    fp32 products and fp32 running sums (numpy float32 matmuls; h and y rounded to fp32).
+    Accumulated round-off is a few 1e-7 of a row's typical magnitude, so the per-row max-norm
+    error is far below 1e-5, while an element 1000 times smaller than the tensor maximum sees
+    that same absolute error 1000 times larger in relative terms: the element-wise measure
+    floored at 1e-3 of the maximum cannot reach 1e-5 in fp32 arithmetic.  The GPU tests
+    therefore assert the floored measure at 1e-3 (and print it), the row measure at 1e-5."""
+    rng = np.random.default_rng(1)
+    T, d, f, E, k = 64, 256, 512, 8, 2
+    f32 = np.float32
+    x = (rng.normal(size=(T, d)) * 0.02).astype(f32)
+    wr = (rng.normal(size=(E, d)) * 0.1).astype(f32)
+    wg = (rng.normal(size=(E, f, d)) * 0.02).astype(f32)
+    wu = (rng.normal(size=(E, f, d)) * 0.02).astype(f32)
+    wd = (rng.normal(size=(E, d, f)) * 0.02).astype(f32)
+    w64 = [a.astype(np.float64) for a in (x, wr, wg, wu, wd)]
+    want = orc.moe_layer_brute_force(*w64, k)
+    idx, w, _ = orc.route_topk(w64[0], w64[1], k)
+    got = np.zeros((T, d), dtype=f32)
+    for t in range(T):
+        for s in range(k):
+            e = idx[t, s]
+            g = wg[e] @ x[t]
+            h = (g / (f32(1) + np.exp(-g))) * (wu[e] @ x[t])
+            got[t] += f32(w[t, s]) * (wd[e] @ h)
+    row = _row_err(got.astype(np.float64), want)
+    elem = floored_rel_err(got.astype(np.float64), want, floor_frac=1e-3)
+    print(f"fp32 arithmetic: per-row err {row:.2e}, floored element-wise err {elem:.2e}")
+    assert row < 1e-5, row
+    assert 1e-5 < elem < 1e-3, elem
