@@ -3,15 +3,23 @@
 
 A step is one pass of the whole hot path over one batch of synthetic input that is already
 resident in HBM: moe_route_topk -> moe_permute -> moe_expert_up_swiglu_gather -> moe_expert_down ->
-moe_combine -> spec_accept.  Prints ONE JSON line: tokens/s of the whole step, the roofline
-figure of the gate/up expert GEMM (HIP events around it), and the CPU oracle's rate on a bounded
-sample of the same batch.
+moe_combine -> spec_accept.  Prints ONE JSON line: tokens/s of the whole step, the per-kernel
+split (HIP events on the launch stream, medians over the timed steps) with both roofline
+fractions of the two expert GEMMs, the same for the other configurations (`also`), the paper's
+own quantities measured on this layer (lambda, c and the Eq. 2 estimate), and the CPU oracle's
+rate on a bounded sample of the same batch.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..6] [--no-cpu-baseline]
+    python bench.py --mode peaks          measured ceilings of this machine (MFMA, HBM, L2 -> LDS)
+    python bench.py --mode speculation    speculation-phase / verification-rule kernels
+    python bench.py --mode traffic        short run to collect HBM traffic counters under rocprofv3
+    python bench.py --mode traffic-report <pmc csv> ...   turns those counters into profiles/traffic.json
 """
 import argparse
+import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -132,6 +140,345 @@ def speculation_bench(args):
                       "mean_accept_len_sampling": float(alen.float().mean().item()), "kernels": res}))
 
 
+PAPER_CONTEXT = {       # the paper's own figures, other hardware: context only, never a target
+    "throughput_speedup_max": 4.30, "hardware": "H100 96 GB + host DRAM over PCIe 5.0 (expert offloading)",
+    "lambda_B1_gamma8": 6.0, "lambda_B32": 2.0, "cite": "Sec. 3.3; abstract"}
+
+
+def speculative_speedup(tau, gamma, c, lam=1.0):
+    """Eq. 2 of the paper: S = tau / (gamma * c + lambda); lambda = 1 gives Eq. 1."""
+    return float(tau) / (float(gamma) * float(c) + float(lam))
+
+
+def source_fingerprint():
+    """sha256 over the kernel sources: ties a stored counter figure to the build it was taken on."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2604_10152_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+KERNELS = ("route", "permute", "up", "down", "combine", "accept")
+
+
+def algorithmic_work(cfg, T, active):
+    """Flops and bytes every kernel of one layer has to do at T tokens (algorithmic: the
+    active experts' weights once, activations and intermediates read and written once)."""
+    es = 4 if cfg.dtype == "f32" else 2
+    d, f, E, k = cfg.d_model, cfg.d_ff, cfg.E, cfg.k
+    P = T * k
+    return {
+        "route": {"flops": 2.0 * T * d * E, "bytes": (T * d + E * d) * es + P * 8},
+        "permute": {"flops": 0.0, "bytes": P * 4 * 3 + (E + 1) * 4},
+        "up": {"flops": 4.0 * P * d * f, "bytes": (active * 2 * d * f + T * d + P * f) * es},
+        "down": {"flops": 2.0 * P * d * f, "bytes": (active * d * f + P * f + P * d) * es},
+        "combine": {"flops": 2.0 * P * d, "bytes": (P * d + T * d) * es + P * 8},
+        "accept": {"flops": 0.0, "bytes": cfg.B * (2 * cfg.gamma + 2) * 4 * 2},
+    }
+
+
+class LayerRun:
+    """One layer configuration set up for timing: buffers, token ids, the step closure."""
+
+    def __init__(self, torch, sm, synth, cfg, L, T=None, B=None, gamma=None, seed=0, draft_remap=None):
+        self.torch, self.sm, self.cfg, self.L = torch, sm, cfg, L
+        self.T = cfg.T if T is None else T
+        self.B = cfg.B if B is None else B
+        self.gamma = cfg.gamma if gamma is None else gamma
+        self.x = L["x"][:self.T].contiguous()
+        self.layer = sm.MoEVerifyLayer(self.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
+                                       renorm=cfg.renorm)
+        draft, target = synth.make_tokens(cfg, seed=seed, B=self.B, gamma=self.gamma)
+        self.draft, self.target = draft, target
+        self.draft_d, self.target_d = draft.cuda(), target.cuda()
+        self.alen = torch.empty(self.B, dtype=torch.int32, device="cuda")
+        self.toks = torch.empty(self.B, self.gamma + 1, dtype=torch.int32, device="cuda")
+        self.stream = torch.cuda.current_stream()
+        self.draft_remap = draft_remap
+
+    def step(self, marks=None):
+        L = self.L
+        self.layer.forward(self.x, L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
+                           stream=self.stream, marks=marks, draft_remap=self.draft_remap)
+        self.sm.spec_accept(self.draft_d, self.target_d, self.alen, self.toks, self.stream)
+        if marks is not None:
+            marks[6].record(self.stream)
+
+    def measure(self, steps, warmup):
+        """W untimed steps, then exactly K steps between two synchronisations (wall clock);
+        inside, seven HIP events per step on the launch stream give the per-kernel times."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        marks = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(marks[i])
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        per = {n: [] for n in KERNELS}
+        whole = []
+        for m in marks:
+            for j, n in enumerate(KERNELS):
+                per[n].append(m[j].elapsed_time(m[j + 1]))
+            whole.append(m[0].elapsed_time(m[6]))
+        counts = (self.layer.expert_offsets[1:] - self.layer.expert_offsets[:-1]).cpu()
+        active = int((counts > 0).sum())
+        work = algorithmic_work(self.cfg, self.T, active)
+        kernels = {}
+        for n in KERNELS:
+            ms = statistics.median(per[n])
+            w = work[n]
+            e = {"us": ms * 1e3, "bytes": w["bytes"], "gbs": w["bytes"] / (ms * 1e-3) / 1e9,
+                 "hbm_frac": w["bytes"] / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+            if n in ("up", "down"):
+                e["flops"] = w["flops"]
+                e["tflops"] = w["flops"] / (ms * 1e-3) / 1e12
+                e["mfma_frac"] = e["tflops"] / (PEAK_BF16_TFLOPS if self.cfg.dtype == "bf16"
+                                                else PEAK_FP32_TFLOPS)
+                e["us_min"], e["us_max"] = min(per[n]) * 1e3, max(per[n]) * 1e3
+            kernels[n] = e
+        return {"ms_per_step": wall_ms, "ms_per_step_median": statistics.median(whole),
+                "kernels": kernels, "active_experts": active,
+                "max_rows_per_expert": int(counts.max()), "min_rows_per_expert": int(counts.min())}
+
+
+def kernel_name(cfg, T):
+    """Which gate/up kernel the library's dispatch picks for this shape (names for the report)."""
+    if cfg.dtype != "bf16":
+        return "grouped_gemm_f32_kernel<true> (gate/up + SwiGLU)"
+    rows = T * cfg.k
+    if rows >= 192 * cfg.E:
+        return "grouped_gemm_bf16_pipe16_kernel<PipeCfg<320,256,32,4,2,4,true>> (gate/up + SwiGLU)"
+    if cfg.d_model >= 4096 and rows >= 48 * cfg.E:
+        return "grouped_gemm_bf16_pipe_kernel<PipeCfg<128,128,64,4,2,2,true>> (gate/up + SwiGLU)"
+    if cfg.d_model >= 4096:
+        return "grouped_gemm_bf16_pipe_kernel<PipeCfg<64,128,64,4,1,2,true>> (gate/up + SwiGLU)"
+    return "grouped_gemm_bf16_kernel<TileCfg<64,256,1,4,true>> (gate/up + SwiGLU)"
+
+
+def roofline_of(cfg, T, m, mfma_bound):
+    up = m["kernels"]["up"]
+    if cfg.dtype != "bf16":
+        r = {"bound": "alu", "achieved": up["tflops"], "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s"}
+    elif mfma_bound:
+        r = {"bound": "mfma", "achieved": up["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        r = {"bound": "hbm", "achieved": up["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    r["frac"] = r["achieved"] / r["peak"]
+    r["kernel"] = kernel_name(cfg, T)
+    r["kernel_ms"] = up["us"] * 1e-3
+    r["traffic"] = None
+    return r
+
+
+def stored_traffic(config_id):
+    """HBM bytes per launch of the gate/up kernel from profiles/traffic.json, but only if that
+    file was written for exactly this build of the kernels; otherwise None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        t = json.load(open(path))
+        if t.get("source_fingerprint") != source_fingerprint():
+            return None
+        return t.get(f"cfg{config_id}", {}).get("up_bytes")
+    except Exception:
+        return None
+
+
+def summary(cfg, T, m):
+    """Compact entry of the `also` block for one configuration."""
+    ms = m["ms_per_step"]
+    flops = 6.0 * T * cfg.k * cfg.d_model * cfg.d_ff + 2.0 * T * cfg.d_model * cfg.E
+    return {"tokens": T, "ms_per_step": ms, "ms_per_step_median": m["ms_per_step_median"],
+            "tokens_per_s": T / (ms * 1e-3), "tflops": flops / (ms * 1e-3) / 1e12,
+            "active_experts": m["active_experts"], "max_rows_per_expert": m["max_rows_per_expert"],
+            "kernels_us": {n: round(m["kernels"][n]["us"], 2) for n in KERNELS},
+            "up": {k: m["kernels"]["up"][k] for k in ("tflops", "mfma_frac", "gbs", "hbm_frac")},
+            "down": {k: m["kernels"]["down"][k] for k in ("tflops", "mfma_frac", "gbs", "hbm_frac")},
+            "roofline": roofline_of(cfg, T, m, mfma_bound=False)}
+
+
+def paper_quantities(torch, sm, synth, cfg, L, B, gamma, steps, warmup, seed, t_verify_ms=None):
+    """lambda, c and the Eq. 2 estimate for this layer at batch size B and draft length gamma
+    (Sec. 3.3): lambda = T<B*(gamma+1)> / T<B> on the same weights, c = T_draft<B> / T_target<B>
+    with the draft model = the same layer restricted to the E/4 most activated experts of the
+    verification pass (nearest-expert substitution), tau = mean generated tokens per step of the
+    synthetic ids (per-position match probability 0.7)."""
+    import dataclasses
+    E, k = cfg.E, cfg.k
+    if t_verify_ms is None:
+        ver = LayerRun(torch, sm, synth, cfg, L, T=B * (gamma + 1), B=B, gamma=gamma, seed=seed)
+        t_verify_ms = ver.measure(steps, warmup)["ms_per_step_median"]
+        offsets = ver.layer.expert_offsets
+    else:
+        ver = LayerRun(torch, sm, synth, cfg, L, T=B * (gamma + 1), B=B, gamma=gamma, seed=seed)
+        ver.step()
+        offsets = ver.layer.expert_offsets
+    tgt = LayerRun(torch, sm, synth, cfg, L, T=B, B=B, gamma=gamma, seed=seed)
+    t_target_ms = tgt.measure(steps, warmup)["ms_per_step_median"]
+    n_draft = max(k, E // 4)
+    table = torch.empty((E, E), dtype=torch.float32, device="cuda")
+    ws = torch.empty((sm.moe_affinity_table_workspace_bytes(E),), dtype=torch.uint8, device="cuda")
+    sm.moe_affinity_table(L["w_gate"], L["w_up"], L["w_down"], table, ws)
+    hot = torch.empty((n_draft,), dtype=torch.int32, device="cuda")
+    remap = torch.empty((E,), dtype=torch.int32, device="cuda")
+    sm.moe_hot_experts(offsets, hot)
+    sm.moe_nearest_draft_expert(table, hot, remap)
+    drf = LayerRun(torch, sm, synth, cfg, L, T=B, B=B, gamma=gamma, seed=seed, draft_remap=remap)
+    t_draft_ms = drf.measure(steps, warmup)["ms_per_step_median"]
+    # tau: synthetic acceptance with match probability 0.7 through spec_accept
+    ids_cfg = dataclasses.replace(cfg, match_prob=0.7)
+    d_ids, t_ids = synth.make_tokens(ids_cfg, seed=seed, B=max(B, 4096), gamma=gamma)
+    alen = torch.empty(d_ids.shape[0], dtype=torch.int32, device="cuda")
+    toks = torch.empty(d_ids.shape[0], gamma + 1, dtype=torch.int32, device="cuda")
+    sm.spec_accept(d_ids.cuda(), t_ids.cuda(), alen, toks)
+    tau = float(alen.float().mean().item())
+    lam, c = t_verify_ms / t_target_ms, t_draft_ms / t_target_ms
+    return {"B": B, "gamma": gamma, "tokens_verified": B * (gamma + 1), "draft_experts": n_draft,
+            "T_target_B_ms": t_target_ms, "T_verify_ms": t_verify_ms, "T_draft_B_ms": t_draft_ms,
+            "lambda": lam, "c": c, "tau_synthetic_p0.7": tau,
+            "S_eq2": speculative_speedup(tau, gamma, c, lam),
+            "S_eq1_lambda_1": speculative_speedup(tau, gamma, c, 1.0)}
+
+
+def peaks_bench(args):
+    """Measured ceilings of this machine, one JSON line each, the published peak beside them."""
+    import torch
+    from paper_2604_10152_amd import peaks
+    torch.cuda.set_device(0)
+    st = torch.cuda.current_stream()
+    out = torch.empty(2048 * 512, dtype=torch.float32, device="cuda")
+    clocks = torch.zeros(2, dtype=torch.int64, device="cuda")
+
+    def timed(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            r = fn()
+            e1.record(st)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = (ms, r) if best is None or ms < best[0] else best
+        return best
+
+    for kind, name in ((0, "v_mfma_f32_16x16x32_bf16"), (1, "v_mfma_f32_32x32x16_bf16")):
+        for blocks in (256, 512):
+            ms, flops = timed(lambda: peaks.mfma(kind, blocks, 20000, out, clocks, st))
+            c = clocks.cpu().tolist()
+            print(json.dumps({"peak": "mfma_bf16_registers_only", "instruction": name,
+                              "workgroups": blocks, "waves_per_simd": 2, "operands": "pseudo-random, "
+                              "12 distinct fragments cycled every instruction",
+                              "ms": ms, "measured_tflops": flops / ms / 1e9,
+                              "published_tflops": PEAK_BF16_TFLOPS,
+                              "frac_of_published": flops / ms / 1e9 / PEAK_BF16_TFLOPS,
+                              "shader_clock_mhz_under_load": c[0] / max(c[1], 1) * 100.0}), flush=True)
+    buf = torch.zeros(4 << 30, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    for blocks in (2048, 8192):
+        ms, nbytes = timed(lambda: peaks.hbm_read(buf, blocks, sink, st))
+        print(json.dumps({"peak": "hbm_read_stream", "buffer_bytes": nbytes, "workgroups": blocks,
+                          "ms": ms, "measured_gbs": nbytes / ms / 1e6, "published_gbs": PEAK_HBM_GBS,
+                          "frac_of_published": nbytes / ms / 1e6 / PEAK_HBM_GBS}), flush=True)
+    for seg in (1024, 128, 64):
+        for region in (16 << 20, 4 << 30):
+            # L2: 1024 workgroups sweep windows inside 16 MB 200 times; HBM: 16384 workgroups
+            # read their own 256 KB window of a 4 GiB buffer exactly once
+            l2 = region <= (64 << 20)
+            blocks, iters = (1024, 200) if l2 else (region // (256 << 10), 1)
+            ms, nbytes = timed(lambda: peaks.l2_lds(buf, region, blocks, iters, seg, st))
+            print(json.dumps({"peak": "global_load_lds_dwordx4_stream",
+                              "source": "L2-resident windows" if l2 else "HBM (4 GiB read once)",
+                              "contiguous_bytes_per_row_piece": seg, "workgroups": blocks, "ms": ms,
+                              "bytes": nbytes, "measured_gbs": nbytes / ms / 1e6,
+                              "published_hbm_gbs": PEAK_HBM_GBS}), flush=True)
+
+
+def traffic_run(args):
+    """What rocprofv3 --pmc is pointed at: two calibration launches of known traffic (a 2 GiB
+    read-only stream with ordinary loads, a 2 GiB global->LDS stream with the expert GEMMs' own
+    load instruction) and three steps of the benchmark workload."""
+    import torch
+    import paper_2604_10152_amd as sm
+    from paper_2604_10152_amd import peaks
+    from workloads import synth
+    torch.cuda.set_device(0)
+    st = torch.cuda.current_stream()
+    buf = torch.zeros(2 << 30, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    flush = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+    flush.add_(1)                                                   # pushes buf out of the caches
+    peaks.hbm_read(buf, 8192, sink, st)
+    flush.add_(1)
+    peaks.l2_lds(buf, 2 << 30, 1024, 8, 128, st)                    # 1024 * 8 * 256 KB = 2 GiB, once
+    torch.cuda.synchronize()
+    cfg = synth.CONFIGS[args.config]
+    L = synth.make_layer(cfg, "cuda", seed=args.seed)
+    run = LayerRun(torch, sm, synth, cfg, L, seed=args.seed)
+    for _ in range(3):
+        run.step()
+    torch.cuda.synchronize()
+    print(json.dumps({"mode": "traffic", "config": args.config, "calibration_bytes": 2 << 30,
+                      "source_fingerprint": source_fingerprint()}))
+
+
+def traffic_report(args):
+    """Reads rocprofv3 counter CSVs (TCC_EA0_RDREQ_sum, TCC_EA0_RDREQ_32B_sum,
+    TCC_EA0_RDREQ_128B_sum in one run; TCC_EA0_WRREQ_sum, TCC_EA0_WRREQ_64B_sum in another) of
+    `--mode traffic` and writes profiles/traffic.json: bytes per launch of the expert GEMMs,
+    each scaled by what the same counters read for the calibration launch of known size."""
+    import csv
+    import collections
+    vals = collections.defaultdict(lambda: collections.defaultdict(list))
+    for path in args.csv:
+        for r in csv.DictReader(open(path)):
+            vals[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+
+    def mean(kname_part, counter, extra=None):
+        for k, d in vals.items():
+            if kname_part in k and (extra is None or extra in k) and counter in d:
+                return sum(d[counter]) / len(d[counter])
+        return None
+
+    def read_bytes(part, extra=None):
+        rd, r32, r128 = (mean(part, c, extra) for c in
+                         ("TCC_EA0_RDREQ_sum", "TCC_EA0_RDREQ_32B_sum", "TCC_EA0_RDREQ_128B_sum"))
+        if rd is None:
+            return None
+        return 128.0 * r128 + 32.0 * r32 + 64.0 * (rd - r128 - r32)
+
+    def write_bytes(part, extra=None):
+        wr, w64 = (mean(part, c, extra) for c in ("TCC_EA0_WRREQ_sum", "TCC_EA0_WRREQ_64B_sum"))
+        if wr is None:
+            return None
+        return 64.0 * w64 + 32.0 * (wr - w64)
+
+    known = float(2 << 30)
+    cal_plain, cal_dma = read_bytes("hbm_read_loop"), read_bytes("l2_lds_loop")
+    out = {"source_fingerprint": source_fingerprint(),
+           "calibration": {"known_bytes": known, "plain_load_stream_read": cal_plain,
+                           "lds_dma_stream_read": cal_dma,
+                           "factor_plain": cal_plain / known if cal_plain else None,
+                           "factor_lds_dma": cal_dma / known if cal_dma else None}}
+    fac = (cal_dma / known) if cal_dma else 1.0
+    entry = {}
+    for tag, extra in (("up", "Lb1E"), ("down", "Lb0E")):
+        rb, wb = read_bytes("grouped_gemm_bf16", extra), write_bytes("grouped_gemm_bf16", extra)
+        entry[f"{tag}_read_bytes"] = rb / fac if rb is not None else None
+        entry[f"{tag}_write_bytes"] = wb
+        entry[f"{tag}_bytes"] = (rb / fac if rb is not None else 0.0) + (wb or 0.0)
+    out[f"cfg{args.config}"] = entry
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    json.dump(out, open(path, "w"), indent=1)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,23 +487,26 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6])
     ap.add_argument("--seed", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", choices=["verify", "speculation"], default="verify",
+    ap.add_argument("--mode", choices=["verify", "speculation", "peaks", "traffic", "traffic-report"],
+                    default="verify",
                     help="verify (default): the MoE verify layer, the line the harness reads; "
-                         "speculation: per-kernel timings of the draft-routing / sampling rows")
+                         "speculation: per-kernel timings of the draft-routing / sampling rows; "
+                         "peaks: measured MFMA / HBM / L2->LDS ceilings of this box; traffic: the "
+                         "short run rocprofv3 --pmc is pointed at; traffic-report: summarises its CSVs")
+    ap.add_argument("csv", nargs="*", help="counter CSV files (traffic-report only)")
     ap.add_argument("--no-also", action="store_true",
-                    help="skip the extra 80-token measurement that the default line carries")
+                    help="skip the other configurations and the paper's quantities (main line only)")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a captured HIP graph (one launch per step); the "
-                         "gate/up kernel time for the roofline then comes from an eager pass "
-                         "run right after the timed region")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="after the timed region, run one 1 GiB device copy (a kernel of known "
-                         "traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE against)")
+                         "per-kernel times then come from an eager pass after the timed region")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.mode == "traffic-report":
+        traffic_report(args)
+        return
 
     import torch
     import paper_2604_10152_amd as sm
@@ -165,178 +515,172 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    sm.load_library()
+    torch.cuda.set_device(0)
     if args.mode == "speculation":
         speculation_bench(args)
         return
-    sm.load_library()
-    torch.cuda.set_device(0)
+    if args.mode == "peaks":
+        peaks_bench(args)
+        return
+    if args.mode == "traffic":
+        traffic_run(args)
+        return
     cfg = synth.CONFIGS[args.config]
-    stacked = cfg.n_layers > 1
-    if stacked:
-        x0, layers = synth.make_stack(cfg, "cuda", seed=args.seed)
-        L = dict(layers[0], x=x0)
-    else:
-        L = synth.make_layer(cfg, "cuda", seed=args.seed)
+    if cfg.n_layers > 1:
+        out = stack_bench(torch, sm, synth, cfg, args)
+        print(json.dumps(out))
+        return
+    L = synth.make_layer(cfg, "cuda", seed=args.seed)
+    run = LayerRun(torch, sm, synth, cfg, L, seed=args.seed)
+    if args.graph:
+        graphed = sm.GraphedStep(lambda st: (
+            run.layer.forward(run.x, L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
+                              stream=st),
+            sm.spec_accept(run.draft_d, run.target_d, run.alen, run.toks, st)))
+        for _ in range(max(1, args.warmup // 2)):
+            graphed.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graphed.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    m = run.measure(args.steps, args.warmup)
+    ms_per_step = graph_ms if args.graph else m["ms_per_step"]
+    d, f = cfg.d_model, cfg.d_ff
+    flops = cfg.flops()
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+    mfma_bound = cfg.dtype == "bf16" and args.config == 4
+    roof = roofline_of(cfg, cfg.T, m, mfma_bound)
+    roof["traffic"] = stored_traffic(args.config)
+    hbm_bytes = sum(m["kernels"][n]["bytes"] for n in KERNELS)
+    out = {
+        "metric": "expert_layer_tokens_per_s", "value": cfg.T / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "ms_per_step_median": m["ms_per_step_median"],
+        "tokens_per_s_median": cfg.T / (m["ms_per_step_median"] * 1e-3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "gamma": cfg.gamma, "tokens": cfg.T,
+                   "d_model": d, "d_ff": f, "experts": cfg.E, "top_k": cfg.k,
+                   "active_experts": m["active_experts"],
+                   "max_rows_per_expert": m["max_rows_per_expert"],
+                   "min_rows_per_expert": m["min_rows_per_expert"]},
+        "launch": "hip-graph" if args.graph else "eager",
+        "tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else None,
+        "hbm_frac": hbm_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "roofline": roof,
+        "kernels": m["kernels"],
+        "paper_context": PAPER_CONTEXT,
+    }
+    if args.config == 4 and not args.graph and not args.no_also:
+        also = {}
+        steps2 = max(10, args.steps // 2)
+        # same weights, the 80-token batch of the Mixtral-shaped configuration (B=16, gamma=4):
+        # the memory-bound end of the same layer
+        c2 = synth.CONFIGS[2]
+        r2 = LayerRun(torch, sm, synth, c2, L, seed=args.seed)
+        also[c2.name] = summary(c2, c2.T, r2.measure(steps2, args.warmup))
+        out["paper_quantities"] = [
+            paper_quantities(torch, sm, synth, c2, L, c2.B, c2.gamma, steps2, 5, args.seed,
+                             t_verify_ms=also[c2.name]["ms_per_step_median"]),
+            paper_quantities(torch, sm, synth, cfg, L, cfg.B, cfg.gamma, steps2, 5, args.seed,
+                             t_verify_ms=m["ms_per_step_median"]),
+        ]
+        del r2
+        for cid in (3, 6):
+            cc = synth.CONFIGS[cid]
+            Lc = synth.make_layer(cc, "cuda", seed=cid)
+            rc = LayerRun(torch, sm, synth, cc, Lc, seed=cid)
+            also[cc.name] = summary(cc, cc.T, rc.measure(steps2, args.warmup))
+            del Lc, rc
+            torch.cuda.empty_cache()
+        out["also"] = also
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, L, run.draft, run.target)
+    if args.config == 4 and not args.graph and not args.no_also:
+        del L, run
+        torch.cuda.empty_cache()
+        c5 = synth.CONFIGS[5]
+        s5 = stack_bench(torch, sm, synth, c5, argparse.Namespace(steps=10, warmup=3, seed=5, graph=False))
+        out["also"][c5.name] = {k: s5[k] for k in ("ms_per_step", "ms_per_step_median", "value", "unit",
+                                                   "accepted_tokens_per_s", "mean_accept_len",
+                                                   "hbm_frac", "tflops", "kernels_us_first_layer")}
+        out["also"][c5.name]["layers"] = c5.n_layers
+    print(json.dumps(out))
+
+
+def stack_bench(torch, sm, synth, cfg, args):
+    """The multi-layer configuration: per layer RMSNorm + MoE verify layer (+ residual), then
+    spec_accept; reports end-to-end verify-step latency and accepted tokens per second."""
+    x0, layers = synth.make_stack(cfg, "cuda", seed=args.seed)
     draft, target = synth.make_tokens(cfg, seed=args.seed)
     draft_d, target_d = draft.cuda(), target.cuda()
     alen = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
     toks = torch.empty(cfg.B, cfg.gamma + 1, dtype=torch.int32, device="cuda")
     stream = torch.cuda.current_stream()
-    if stacked:
-        stack = sm.MoEVerifyStack(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
-                                  renorm=cfg.renorm)
-        layer = stack.layer
+    stack = sm.MoEVerifyStack(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
+                              renorm=cfg.renorm)
 
-        def step(ev=None):
-            stack.forward(x0, layers, stream=stream, up_events=ev)
-            sm.spec_accept(draft_d, target_d, alen, toks, stream)
-    else:
-        layer = sm.MoEVerifyLayer(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.torch_dtype,
-                                  renorm=cfg.renorm)
-
-        def step(ev=None):
-            layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
-                          stream=stream, up_events=ev)
-            sm.spec_accept(draft_d, target_d, alen, toks, stream)
+    def step(marks=None, ends=None):
+        if ends is not None:
+            ends[0].record(stream)
+        stack.forward(x0, layers, stream=stream, marks=marks)
+        sm.spec_accept(draft_d, target_d, alen, toks, stream)
+        if ends is not None:
+            ends[1].record(stream)
 
     for _ in range(args.warmup):
         step()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
-    if args.graph:
-        if stacked:
-            graphed = sm.GraphedStep(lambda st: (stack.forward(x0, layers, stream=st),
-                                                 sm.spec_accept(draft_d, target_d, alen, toks, st)))
-        else:
-            graphed = sm.GraphedStep(lambda st: (
-                layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
-                              stream=st),
-                sm.spec_accept(draft_d, target_d, alen, toks, st)))
-        for _ in range(max(1, args.warmup // 2)):
-            graphed.replay()
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    ends = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    if getattr(args, "graph", False):
+        graphed = sm.GraphedStep(lambda st: (stack.forward(x0, layers, stream=st),
+                                             sm.spec_accept(draft_d, target_d, alen, toks, st)))
+        graphed.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(args.steps):
+        for _ in range(args.steps):
             graphed.replay()
         torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for i in range(args.steps):            # kernel time for the roofline: eager, untimed
-            step(events[i])
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        for i in range(args.steps):
+            step(marks[i], ends[i])
         torch.cuda.synchronize()
     else:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
-            step(events[i])
+            step(marks[i], ends[i])
         torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    up_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
-
-    counts = (layer.expert_offsets[1:] - layer.expert_offsets[:-1]).cpu()
-    active = int((counts > 0).sum())
-    esize = 4 if cfg.dtype == "f32" else 2
-    P, d, f = cfg.P, cfg.d_model, cfg.d_ff
-    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
-    tflops = cfg.flops() * cfg.n_layers / (ms_per_step * 1e-3) / 1e12
-
-    # dominant kernel: the gate/up expert GEMM with the SwiGLU epilogue (2/3 of the flops)
-    up_flops = 4.0 * P * d * f
-    # bytes: the active experts' two matrices once, every x row once (the gather re-reads hit
-    # the cache), h once
-    up_bytes = (active * 2 * d * f + cfg.T * d + P * f) * esize
-    if cfg.dtype == "bf16" and args.config == 4:
-        roof = {"bound": "mfma", "achieved": up_flops / (up_ms * 1e-3) / 1e12,
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
-    elif cfg.dtype == "bf16":
-        roof = {"bound": "hbm", "achieved": up_bytes / (up_ms * 1e-3) / 1e9,
-                "peak": PEAK_HBM_GBS, "unit": "GB/s"}
-    else:
-        roof = {"bound": "alu", "achieved": up_flops / (up_ms * 1e-3) / 1e12,
-                "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    if cfg.dtype != "bf16":
-        roof["kernel"] = "grouped_gemm_f32_kernel<true> (gate/up + SwiGLU)"
-    elif args.config == 4:
-        roof["kernel"] = "grouped_gemm_bf16_pipe16_kernel<PipeCfg<320,256,32,4,2,4,true>> (gate/up + SwiGLU)"
-    elif d >= 4096:
-        roof["kernel"] = "grouped_gemm_bf16_pipe_kernel<PipeCfg<64,128,64,4,1,2,true>> (gate/up + SwiGLU)"
-    else:
-        roof["kernel"] = "grouped_gemm_bf16_kernel<TileCfg<64,256,1,4,true>> (gate/up + SwiGLU)"
-    roof["kernel_ms"] = up_ms
-    roof["traffic"] = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            roof["traffic"] = json.load(open(tpath)).get(f"cfg{args.config}")
-        except Exception:
-            roof["traffic"] = None
-
-    out = {
-        "metric": "expert_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
-        "data": "synthetic",
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    med = statistics.median(a.elapsed_time(b) for a, b in ends)
+    names = ("route", "permute", "up", "down", "combine")
+    k_us = {n: round(statistics.median(m[j].elapsed_time(m[j + 1]) for m in marks) * 1e3, 2)
+            for j, n in enumerate(names)}
+    es = 2 if cfg.dtype == "bf16" else 4
+    weight_bytes = cfg.n_layers * 3.0 * cfg.E * cfg.d_model * cfg.d_ff * es
+    return {
+        "metric": "verify_step_accepted_tokens_per_s", "value": float(alen.sum().item()) / (ms * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "ms_per_step_median": med, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "gamma": cfg.gamma, "tokens": cfg.T,
-                   "d_model": d, "d_ff": f, "experts": cfg.E, "top_k": cfg.k,
-                   "active_experts": active, "max_rows_per_expert": int(counts.max())},
-        "launch": "hip-graph" if args.graph else "eager",
-        "tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else None,
-        "roofline": roof,
+                   "d_model": cfg.d_model, "d_ff": cfg.d_ff, "experts": cfg.E, "top_k": cfg.k,
+                   "layers": cfg.n_layers},
+        "launch": "hip-graph" if getattr(args, "graph", False) else "eager",
+        "accepted_tokens_per_s": float(alen.sum().item()) / (ms * 1e-3),
+        "verified_tokens_per_s": cfg.T / (ms * 1e-3),
+        "mean_accept_len": float(alen.float().mean().item()),
+        "tflops": cfg.flops() * cfg.n_layers / (ms * 1e-3) / 1e12,
+        "hbm_frac": weight_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "roofline": {"bound": "hbm", "achieved": weight_bytes / (ms * 1e-3) / 1e9,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": weight_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "kernel": "whole step (weights of all layers streamed once)", "traffic": None},
+        "kernels_us_first_layer": k_us,
     }
-    if args.config == 4 and not args.graph and not args.no_also:
-        # same weights, the 80-token batch of the Mixtral-shaped configuration (B=16, gamma=4):
-        # the memory-bound end of the same layer, reported beside the headline workload
-        c2 = synth.CONFIGS[2]
-        x2 = L["x"][:c2.T].contiguous()
-        lay2 = sm.MoEVerifyLayer(c2.T, d, f, cfg.E, cfg.k, cfg.torch_dtype, renorm=cfg.renorm)
-        d2, t2 = synth.make_tokens(c2, seed=args.seed)
-        d2, t2 = d2.cuda(), t2.cuda()
-        al2 = torch.empty(c2.B, dtype=torch.int32, device="cuda")
-        tk2 = torch.empty(c2.B, c2.gamma + 1, dtype=torch.int32, device="cuda")
-        ev2 = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for _ in range(args.steps)]
-
-        def step2(ev=None):
-            lay2.forward(x2, L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
-                         stream=stream, up_events=ev)
-            sm.spec_accept(d2, t2, al2, tk2, stream)
-
-        for _ in range(args.warmup):
-            step2()
-        torch.cuda.synchronize()
-        ta = time.perf_counter()
-        for i in range(args.steps):
-            step2(ev2[i])
-        torch.cuda.synchronize()
-        ms2 = (time.perf_counter() - ta) * 1e3 / args.steps
-        up2 = sum(a.elapsed_time(b) for a, b in ev2) / args.steps
-        act2 = int(((lay2.expert_offsets[1:] - lay2.expert_offsets[:-1]) > 0).sum())
-        bytes2 = (act2 * 2 * d * f + c2.T * d + c2.P * f) * esize
-        out["also"] = {c2.name: {
-            "tokens": c2.T, "ms_per_step": ms2, "tokens_per_s": c2.T / (ms2 * 1e-3),
-            "tflops": c2.flops() / (ms2 * 1e-3) / 1e12,
-            "roofline": {"bound": "hbm", "achieved": bytes2 / (up2 * 1e-3) / 1e9,
-                         "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": bytes2 / (up2 * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                         "kernel": "grouped_gemm_bf16_pipe_kernel<PipeCfg<64,128,64,4,1,2,true>> "
-                                   "(gate/up + SwiGLU)", "kernel_ms": up2}}}
-    if stacked:
-        out["config"]["layers"] = cfg.n_layers
-        out["accepted_tokens_per_s"] = float(alen.sum().item()) / (ms_per_step * 1e-3)
-        out["mean_accept_len"] = float(alen.float().mean().item())
-        args.no_cpu_baseline = True      # the bounded oracle sample is defined for one layer
-    if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
-        dst = torch.empty_like(src)
-        flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()   # evicts src
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst, flush
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, L, draft, target)
-    print(json.dumps(out))
 
 
 if __name__ == "__main__":

@@ -34,32 +34,41 @@ class MoEVerifyLayer:
         self.h = torch.empty((P, d_ff), dtype=dtype, device=dev)
 
     def forward(self, x, w_router, w_gate, w_up, w_down, bias=None, residual=None, out=None,
-                stream=None, up_events=None, draft_remap=None):
-        """Enqueues the layer.  `up_events`, if given, is a (start, end) pair of torch events
-        recorded around the gate/up expert GEMM (used by the benchmark's roofline figure).
+                stream=None, marks=None, draft_remap=None):
+        """Enqueues the layer.  `marks`, if given, is a sequence of six torch events recorded on
+        `stream` before the router and after each of the five calls (route, permute, gate/up,
+        down, combine): the benchmark's per-kernel times.
         `draft_remap` ([E] int32 from moe_nearest_draft_expert) switches to the draft model's
         routing: selected experts that are not resident are replaced by their nearest draft
         expert, so only draft experts compute."""
         out = self.out if out is None else out
+        if marks is not None:
+            marks[0].record(stream)
         if draft_remap is None:
             B.moe_route_topk(x, w_router, bias, self.k, self.renorm, self.topk_idx, self.topk_w,
                              stream)
         else:
             B.moe_route_topk_draft(x, w_router, bias, self.k, self.renorm, draft_remap,
                                    self.topk_idx, self.topk_w, stream)
+        if marks is not None:
+            marks[1].record(stream)
         B.moe_permute(x, self.topk_idx, self.E, None if self.fuse_gather else self.x_perm,
                       self.expert_offsets, self.row_src, self.row_of, stream)
-        if up_events is not None:
-            up_events[0].record(stream)
+        if marks is not None:
+            marks[2].record(stream)
         if self.fuse_gather:
             B.moe_expert_up_swiglu_gather(x, self.row_src, self.k, self.expert_offsets, w_gate,
                                           w_up, self.h, stream)
         else:
             B.moe_expert_up_swiglu(self.x_perm, self.expert_offsets, w_gate, w_up, self.h, stream)
-        if up_events is not None:
-            up_events[1].record(stream)
+        if marks is not None:
+            marks[3].record(stream)
         B.moe_expert_down(self.h, self.expert_offsets, w_down, self.y_perm, stream)
+        if marks is not None:
+            marks[4].record(stream)
         B.moe_combine(self.y_perm, self.row_of, self.topk_w, residual, out, stream)
+        if marks is not None:
+            marks[5].record(stream)
         return out
 
 
@@ -77,10 +86,10 @@ class MoEVerifyStack:
         self.normed = torch.empty((T, d_model), dtype=dtype, device=dev)
         self.h = [torch.empty((T, d_model), dtype=dtype, device=dev) for _ in range(2)]
 
-    def forward(self, x, layers, keep_hidden=False, stream=None, up_events=None):
+    def forward(self, x, layers, keep_hidden=False, stream=None, marks=None):
         """`layers`: list of dicts with gain, w_router, bias, w_gate, w_up, w_down.
         Returns the final hidden state (and, if keep_hidden, clones of every h_l).
-        `up_events` brackets the gate/up expert GEMM of the first layer (benchmark only)."""
+        `marks`: six events recorded around the calls of the first layer (benchmark only)."""
         hidden = [x.clone()] if keep_hidden else None
         cur = x
         for li, L in enumerate(layers):
@@ -88,7 +97,7 @@ class MoEVerifyStack:
             B.moe_rmsnorm(cur, L["gain"], self.eps, self.normed, stream)
             self.layer.forward(self.normed, L["w_router"], L["w_gate"], L["w_up"], L["w_down"],
                                L.get("bias"), residual=cur, out=nxt, stream=stream,
-                               up_events=up_events if li == 0 else None)
+                               marks=marks if li == 0 else None)
             cur = nxt
             if keep_hidden:
                 hidden.append(cur.clone())
