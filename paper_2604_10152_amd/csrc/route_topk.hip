@@ -1,9 +1,12 @@
 // Gate of one MoE block: router logits in fp64, top-k on logits, softmax gate weights.
 // (SpecMoE Sec. 2.1: the gate selects the top-K experts per token.)
 //
-// A workgroup of 4 wavefronts owns TOK tokens.  The d_model axis is dealt to the 256 lanes in
-// 16-byte chunks (chunk q -> wave (q/64)%4, lane q%64), every lane keeps fp64 partial sums
-// for TOK tokens x EC experts (TOK*EC <= 64), so one router-weight load feeds TOK tokens.
+// A workgroup owns TOK tokens and consists of 4 groups of 4 wavefronts; group g takes the
+// expert chunks g, g+4, ... of EC experts each, so the widening of the router weights to fp64
+// (the bulk of the work: every weight is converted once per workgroup) is spread over 1024
+// lanes.  Inside a group the d_model axis is dealt to its 256 lanes in 16-byte chunks (chunk q
+// -> wave (q/64)%4, lane q%64), every lane keeps fp64 partial sums for TOK tokens x EC experts
+// (TOK*EC <= 16), so one router-weight load feeds TOK tokens.
 // The TOK*EC partial sums of a wave are reduced over its 64 lanes by a transposing butterfly:
 // at the step with lane distance h a lane hands the half of its values that its partner keeps
 // to the partner and adds what it receives, so 63 exchange-and-add steps reduce all values at
@@ -18,8 +21,10 @@
 namespace specmoe {
 namespace {
 
-constexpr int kRouteWaves = 4;
-constexpr int kRouteThreads = kRouteWaves * kWave;
+constexpr int kRouteWaves = 4;                        // wavefronts per group
+constexpr int kGroupThreads = kRouteWaves * kWave;
+constexpr int kRouteGroups = 4;                       // groups per workgroup (split the experts)
+constexpr int kRouteThreads = kRouteGroups * kGroupThreads;
 
 // Transposing butterfly over the 64 lanes of a wave: v[0..CNT) in every lane -> v[0] = total of
 // value (lane * CNT0 / 64) where CNT0 is the count at the first step.
@@ -81,24 +86,31 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
     const T* __restrict__ x, const T* __restrict__ wr, const float* __restrict__ bias, int Tn,
     int d, int E, int k, int renorm, int32_t* __restrict__ idx_out, float* __restrict__ w_out,
     const int32_t* __restrict__ remap /* nullable: draft-mode expert substitution, [E] */) {
-    static_assert(TOK * EC <= kWave && (TOK * EC & (TOK * EC - 1)) == 0, "values per wave");
+    static_assert(TOK * EC <= 16 && (TOK * EC & (TOK * EC - 1)) == 0, "values per wave");
     constexpr int NV = TOK * EC;                      // partial sums per lane and pass
-    extern __shared__ double lds_d[];                 // logits[TOK][E], then part[4][NV]
+    extern __shared__ double lds_d[];                 // logits[TOK][E], then part[groups][4][NV]
     double* logits = lds_d;
-    double* part = lds_d + (size_t)TOK * E;
     typedef Chunk<T, VEC> CH;
     constexpr int V = CH::N;
     constexpr int G = EC < 8 ? EC : 8;                // router rows loaded together
     const int lane = threadIdx.x % kWave;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int group = wave_all / kRouteWaves, wave = wave_all % kRouteWaves;
+    const int gtid = threadIdx.x % kGroupThreads;     // thread index inside the group
+    double* part = lds_d + (size_t)TOK * E + (size_t)group * kRouteWaves * NV;
     const int t0 = blockIdx.x * TOK;
     const int nq = d / V;                             // chunks per row (VEC: d % V == 0)
 
-    for (int e0 = 0; e0 < E; e0 += EC) {
+    // every group runs the same number of passes (the barriers inside are workgroup-wide); a
+    // group whose chunk lies beyond E skips the arithmetic of that pass
+    const int passes = (E + kRouteGroups * EC - 1) / (kRouteGroups * EC);
+    for (int pass = 0; pass < passes; ++pass) {
+        const int e0 = (pass * kRouteGroups + group) * EC;
+        const bool live = e0 < E;
         double acc[NV];                               // index t * EC + c
 #pragma unroll
         for (int i = 0; i < NV; ++i) acc[i] = 0.0;
-        for (int q = threadIdx.x; q < nq; q += kRouteThreads) {
+        for (int q = gtid; live && q < nq; q += kGroupThreads) {
             typename CH::Raw xr[TOK];
 #pragma unroll
             for (int t = 0; t < TOK; ++t)
@@ -129,24 +141,64 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
         constexpr int REP = kWave / NV;               // lanes holding the same value
         if (lane % REP == 0) part[wave * NV + lane / REP] = acc[0];
         __syncthreads();
-        if (threadIdx.x < NV) {
-            const int t = threadIdx.x / EC, c = threadIdx.x % EC;
+        if (gtid < NV) {
+            const int t = gtid / EC, c = gtid % EC;
             if (e0 + c < E) {
-                double s = part[threadIdx.x];
+                double s = part[gtid];
 #pragma unroll
-                for (int w = 1; w < kRouteWaves; ++w) s += part[w * NV + threadIdx.x];
+                for (int w = 1; w < kRouteWaves; ++w) s += part[w * NV + gtid];
                 logits[(size_t)t * E + e0 + c] = s + (bias ? (double)bias[e0 + c] : 0.0);
             }
         }
         __syncthreads();
     }
 
-    // wave t ranks token t0 + t (TOK <= 4 waves)
-    if (wave >= TOK || t0 + wave >= Tn) return;
-    const int t = t0 + wave;
-    const double* logit = logits + (size_t)wave * E;
-    // lane owns experts lane, lane+64, ...; `taken` marks the ones already selected.
-    // Lane s keeps the result of round s (k <= 64), so the final stores are coalesced.
+    // wave t of the workgroup ranks token t0 + t (TOK <= 4)
+    if (wave_all >= TOK || t0 + wave_all >= Tn) return;
+    const int t = t0 + wave_all;
+    const double* logit = logits + (size_t)wave_all * E;
+    if (E <= kWave) {
+        // One expert per lane: every lane counts the experts that beat its own on the key
+        // (logit descending, id ascending) - its rank, i.e. the slot it would fill.  The other
+        // lanes' logits arrive through v_readlane broadcasts (a few cycles each) instead of the
+        // k x 6 dependent cross-lane exchanges of the arg-max rounds below.
+        const bool valid = lane < E;
+        const double v = valid ? logit[lane] : 0.0;
+        const int vlo = (int)(uint32_t)__double_as_longlong(v);
+        const int vhi = (int)(uint32_t)((uint64_t)__double_as_longlong(v) >> 32);
+        auto lane_value = [&](double val, int src) __attribute__((always_inline)) -> double {
+            const long long bits = __double_as_longlong(val);
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, src);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)bits >> 32), src);
+            return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+        };
+        int rank = 0;
+        for (int j = 0; j < E; ++j) {
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(vlo, j);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane(vhi, j);
+            const double vj = __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+            rank += better(vj, j, v, lane) ? 1 : 0;
+        }
+        const int first = __builtin_amdgcn_readfirstlane(
+            __ffsll((long long)__ballot(valid && rank == 0)) - 1);
+        const double vmax = lane_value(v, first);
+        // softmax over all E experts, relative to the largest logit
+        const double pe = valid ? exp(v - vmax) : 0.0;
+        const double p = pe / wave_sum(pe);
+        double wsum_sel = 0.0;                        // slot order, identical on every lane
+        for (int sl = 0; sl < k; ++sl) {
+            const int src = __builtin_amdgcn_readfirstlane(
+                __ffsll((long long)__ballot(valid && rank == sl)) - 1);
+            wsum_sel += lane_value(p, src);
+        }
+        if (valid && rank < k) {
+            idx_out[(size_t)t * k + rank] = remap ? remap[lane] : lane;
+            w_out[(size_t)t * k + rank] = (float)(renorm ? p / wsum_sel : p);
+        }
+        return;
+    }
+    // More than 64 experts: lane owns experts lane, lane+64, ...; `taken` marks the ones already
+    // selected.  Lane s keeps the result of round s (k <= 64), so the final stores are coalesced.
     constexpr int kOwn = 1024 / kWave;                // SPECMOE_MAX_EXPERTS / 64
     uint32_t taken = 0;
     double vmax = 0.0, denom = 1.0, wsum_sel = 0.0, my_p = 0.0;
@@ -189,30 +241,34 @@ template <typename T, bool VEC, int TOK, int EC>
 void launch_variant(const T* x, const T* wr, const float* bias, int Tn, int d, int E, int k,
                     int renorm, int32_t* idx, float* w, const int32_t* remap, hipStream_t s) {
     dim3 grid((Tn + TOK - 1) / TOK), block(kRouteThreads);
-    size_t lds = ((size_t)TOK * E + (size_t)kRouteWaves * TOK * EC) * sizeof(double);
+    size_t lds = ((size_t)TOK * E + (size_t)kRouteGroups * kRouteWaves * TOK * EC) * sizeof(double);
     hipLaunchKernelGGL((route_topk_kernel<T, VEC, TOK, EC>), grid, block, lds, s, x, wr, bias, Tn,
                        d, E, k, renorm, idx, w, remap);
 }
 
-// experts per pass: the smallest of 8/16/32/64 that covers E (64 for more), capped at 64/TOK
+// experts per group and pass: a quarter of E rounded up to a power of two, at most 16 / TOK
 template <typename T, bool VEC, int TOK>
 void launch_by_experts(const T* x, const T* wr, const float* bias, int Tn, int d, int E, int k,
                        int renorm, int32_t* idx, float* w, const int32_t* remap, hipStream_t s) {
-    if (E <= 8 || TOK * 16 > kWave)
-        launch_variant<T, VEC, TOK, (TOK * 8 <= kWave ? 8 : kWave / TOK)>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
-    else if (E <= 16 || TOK * 32 > kWave)
-        launch_variant<T, VEC, TOK, (TOK * 16 <= kWave ? 16 : kWave / TOK)>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
-    else if (E <= 32 || TOK * 64 > kWave)
-        launch_variant<T, VEC, TOK, (TOK * 32 <= kWave ? 32 : kWave / TOK)>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    constexpr int EC_MAX = 16 / TOK;
+    const int quarter = (E + kRouteGroups - 1) / kRouteGroups;
+    if (quarter <= 1)
+        launch_variant<T, VEC, TOK, 1>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else if (quarter <= 2 || EC_MAX == 2)
+        launch_variant<T, VEC, TOK, (EC_MAX < 2 ? EC_MAX : 2)>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else if (quarter <= 4 || EC_MAX == 4)
+        launch_variant<T, VEC, TOK, (EC_MAX < 4 ? EC_MAX : 4)>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else if (quarter <= 8 || EC_MAX == 8)
+        launch_variant<T, VEC, TOK, (EC_MAX < 8 ? EC_MAX : 8)>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
     else
-        launch_variant<T, VEC, TOK, kWave / TOK>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+        launch_variant<T, VEC, TOK, EC_MAX>(x, wr, bias, Tn, d, E, k, renorm, idx, w, remap, s);
 }
 
 template <typename T, int V>
 void launch_typed(const void* x, const void* wr, const float* bias, int Tn, int d, int E, int k,
                   int renorm, int32_t* idx, float* w, const int32_t* remap, hipStream_t s) {
     const bool vec = (d % V == 0) && ((((uintptr_t)x | (uintptr_t)wr) & 15u) == 0);
-    const bool many = Tn >= 1024;                     // enough tokens to fill the chip 4 at a time
+    const bool many = Tn > 256;                       // more tokens than CUs: 4 tokens per workgroup
     const T* xt = (const T*)x;
     const T* wt = (const T*)wr;
     if (vec && many) launch_by_experts<T, true, 4>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);

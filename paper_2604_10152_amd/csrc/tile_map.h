@@ -20,7 +20,7 @@ struct TileLoc {
 };
 
 // Even split: an expert with M rows gets ceil(M / BM_MAX) m-tiles of equal height (rounded up
-// to the 32-row MFMA granule), so no tile is a thin remainder that would stream a whole
+// to the row granule of the matrix instruction in use: 32 or 16), so no tile is a thin remainder that would stream a whole
 // weight tile for a handful of rows.
 struct EvenSplit {
     int mt;    // m-tiles of the expert
