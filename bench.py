@@ -379,6 +379,18 @@ def peaks_bench(args):
                               "published_tflops": PEAK_BF16_TFLOPS,
                               "frac_of_published": flops / ms / 1e9 / PEAK_BF16_TFLOPS,
                               "shader_clock_mhz_under_load": c[0] / max(c[1], 1) * 100.0}), flush=True)
+    lsink = torch.zeros(512 * 16, dtype=torch.uint8, device="cuda")
+    names = ("consecutive 16-byte pieces",
+             "expert GEMM fragment read: 16 rows of 64 bytes, chunk ^ ((row/2)%4)",
+             "all lanes in the same banks",
+             "same fragment read with chunk ^ ((row/4)%4)")
+    for pattern in range(4):
+        peaks.lds_read(pattern, 2000, clocks, lsink, st)
+        torch.cuda.synchronize()
+        c = clocks.cpu().tolist()[0]
+        print(json.dumps({"peak": "lds_ds_read_b128", "pattern": names[pattern],
+                          "clk_per_wave_instruction_per_cu": c / (2000 * 64),
+                          "bytes_per_clk_per_cu": 1024.0 * 2000 * 64 / c}), flush=True)
     buf = torch.zeros(4 << 30, dtype=torch.uint8, device="cuda")
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
     for blocks in (2048, 8192):

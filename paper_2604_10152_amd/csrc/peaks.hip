@@ -146,9 +146,59 @@ __global__ __launch_bounds__(512) void l2_lds_loop(const unsigned char* __restri
     wait_vmcnt<0>();
 }
 
+// ds_read_b128 throughput of one CU for a given lane -> byte-offset pattern: 8 wavefronts, each
+// issues 8 reads (4 KB apart) per pass.  pattern 0: lane * 16 (consecutive, conflict-free by
+// construction); 1: the fragment read of the large-batch expert GEMM (row lane%16 of a 64-byte-row
+// tile, chunk (lane/16) ^ ((row/2)%4)); 2: lane * 256 (every lane in the same banks); 3: as 1 with
+// the term (row/4)%4 (one sweep over the bank groups per 4 rows): a 2-way conflict on gfx950.
+// clocks[0] = shader cycles of the timed loop of wave 0.
+__global__ __launch_bounds__(512) void lds_read_loop(int pattern, int iters, long long* clocks,
+                                                     U128* sink) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
+    const int lane = threadIdx.x % kWave;
+    for (int i = threadIdx.x; i < 65536 / 16; i += blockDim.x)
+        reinterpret_cast<U128*>(lds_raw)[i] = U128{(uint32_t)i, 1, 2, 3};
+    __syncthreads();
+    int off;
+    if (pattern == 0) off = lane * 16;
+    else if (pattern == 1) off = (lane & 15) * 64 + (((lane >> 4) ^ (((lane & 15) / 2) % 4)) << 4);
+    else if (pattern == 3) off = (lane & 15) * 64 + (((lane >> 4) ^ (((lane & 15) / 4) % 4)) << 4);
+    else off = lane * 256;
+    U128 acc = {0, 0, 0, 0};
+    const uint32_t lds_off =
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_raw + (uint32_t)off;
+    const long long c0 = clock64();
+    for (int it = 0; it < iters; ++it) {
+        U128 r[8];
+        asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:4096\n\t"
+                     "ds_read_b128 %2, %8 offset:8192\n\tds_read_b128 %3, %8 offset:12288\n\t"
+                     "ds_read_b128 %4, %8 offset:16384\n\tds_read_b128 %5, %8 offset:20480\n\t"
+                     "ds_read_b128 %6, %8 offset:24576\n\tds_read_b128 %7, %8 offset:28672\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=v"(r[0]), "=v"(r[1]), "=v"(r[2]), "=v"(r[3]), "=v"(r[4]), "=v"(r[5]),
+                       "=v"(r[6]), "=v"(r[7])
+                     : "v"(lds_off)
+                     : "memory");
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= r[u];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && clocks) clocks[0] = clock64() - c0;
+    sink[threadIdx.x] = acc;
+}
+
 }  // namespace
 
 extern "C" {
+
+// One workgroup of 8 wavefronts; `sink` holds 512 x 16 bytes.  clocks[0] / (iters * 64) is the
+// number of shader cycles the CU spends per ds_read_b128 wave-instruction.
+int specmoe_peak_lds_read(int pattern, int iters, long long* clocks, void* sink, void* stream) {
+    if (!sink || iters < 1 || pattern < 0 || pattern > 3) return 1;
+    hipLaunchKernelGGL(lds_read_loop, dim3(1), dim3(512), 65536, (hipStream_t)stream, pattern,
+                       iters, clocks, (U128*)sink);
+    return hipGetLastError() == hipSuccess ? 0 : 5;
+}
 
 // kind 0: v_mfma_f32_16x16x32_bf16, kind 1: v_mfma_f32_32x32x16_bf16.  `out` holds
 // blocks*512 floats, `clocks` two long longs (may be NULL).  Returns the flops of the launch

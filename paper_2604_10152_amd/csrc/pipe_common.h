@@ -15,7 +15,7 @@ struct PipeCfg {
     static constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);   // 32x32 sub-tiles per wave
     static constexpr int KK = BK / 16;                               // MFMA k-steps per stage
     static constexpr int ROW_BYTES = BK * 2, CHUNKS = BK / 8;        // 16-byte chunks per row
-    static constexpr int RPG = 16 / CHUNKS;          // tile rows per sweep over the 16 bank groups
+    static constexpr int RPG = 2;                    // tile rows that share a swizzle term
     static constexpr int ROWS_PER_DMA = 1024 / ROW_BYTES;            // rows one wave-load fills
     static constexpr int A_LOADS = BM / ROWS_PER_DMA;                // wave-loads per stage, A
     static constexpr int A_PW = (A_LOADS + NWAVES - 1) / NWAVES;     // at most, per wave
@@ -36,8 +36,14 @@ struct PipeCfg {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
-// byte offset of 16-byte chunk c of tile row r: conflict-free for 128-bit accesses on the
-// 64-bank LDS (16 consecutive lanes = 16 consecutive rows must hit 16 different bank groups)
+// Byte offset of 16-byte chunk c of tile row r: chunk c sits at position c ^ ((r / 2) % CHUNKS)
+// of its row.  Measured on gfx950 (ds_read_b128, one CU, 8 wavefronts; 4.4 clk per instruction
+// is the conflict-free rate): with 128-byte rows this term is conflict-free for the 32-row
+// fragment reads of the 32x32x16 instruction; with 64-byte rows it is conflict-free for the
+// 16-row reads of the 16x16x32 instruction, where the term (r / 4) % 4 - one sweep over the 16
+// bank groups per 4 rows, the "obvious" choice - costs 8.0 clk per read (SQ_LDS_BANK_CONFLICT =
+// half of SQ_LDS_IDX_ACTIVE) because the hardware pairs lanes 0-7 with lanes 16-23, not with
+// lanes 8-15.
 template <typename C>
 __device__ __forceinline__ int swz(int r, int c) {
     return r * C::ROW_BYTES + ((c ^ ((r / C::RPG) % C::CHUNKS)) << 4);

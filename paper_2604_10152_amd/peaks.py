@@ -21,6 +21,7 @@ def load():
         lib.specmoe_peak_mfma.argtypes = [i, i, i, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
         lib.specmoe_peak_hbm_read.argtypes = [vp, sz, i, vp, vp]
         lib.specmoe_peak_l2_lds.argtypes = [vp, sz, i, i, i, vp]
+        lib.specmoe_peak_lds_read.argtypes = [i, i, vp, vp, vp]
         _LIB = lib
     return _LIB
 
@@ -47,3 +48,8 @@ def l2_lds(buf, region_bytes, blocks, iters, seg, stream):
     _check(load().specmoe_peak_l2_lds(buf.data_ptr(), region_bytes, blocks, iters, seg,
                                       stream.cuda_stream), "specmoe_peak_l2_lds")
     return blocks * iters * (256 << 10)
+
+
+def lds_read(pattern, iters, clocks, sink, stream):
+    _check(load().specmoe_peak_lds_read(pattern, iters, clocks.data_ptr(), sink.data_ptr(),
+                                        stream.cuda_stream), "specmoe_peak_lds_read")
