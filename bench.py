@@ -428,7 +428,7 @@ def traffic_run(args):
     flush.add_(1)                                                   # pushes buf out of the caches
     peaks.hbm_read(buf, 8192, sink, st)
     flush.add_(1)
-    peaks.l2_lds(buf, 2 << 30, 1024, 8, 128, st)                    # 1024 * 8 * 256 KB = 2 GiB, once
+    peaks.l2_lds(buf, 2 << 30, 8192, 1, 128, st)                    # 8192 windows of 256 KB: 2 GiB, each byte once
     torch.cuda.synchronize()
     cfg = synth.CONFIGS[args.config]
     L = synth.make_layer(cfg, "cuda", seed=args.seed)
