@@ -255,7 +255,7 @@ def kernel_name(cfg, T):
     if rows >= 192 * cfg.E:
         return "grouped_gemm_bf16_pipe16_kernel<PipeCfg<320,256,32,4,2,4,true>> (gate/up + SwiGLU)"
     if cfg.d_model >= 4096 and rows >= 48 * cfg.E:
-        return "grouped_gemm_bf16_pipe_kernel<PipeCfg<128,128,64,4,2,2,true>> (gate/up + SwiGLU)"
+        return "grouped_gemm_bf16_pipe16_kernel<PipeCfg<192,256,32,4,2,4,true>> (gate/up + SwiGLU)"
     if cfg.d_model >= 4096:
         return "grouped_gemm_bf16_pipe_kernel<PipeCfg<64,128,64,4,1,2,true>> (gate/up + SwiGLU)"
     return "grouped_gemm_bf16_kernel<TileCfg<64,256,1,4,true>> (gate/up + SwiGLU)"

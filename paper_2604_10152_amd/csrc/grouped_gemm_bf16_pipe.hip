@@ -319,17 +319,9 @@ hipError_t launch_expert_down_bf16_small(const bf16_t* h, const int32_t* offsets
                                                               d, f, y, s);
 }
 
-// In between (tens to a few hundred rows per expert, e.g. 16 experts with top-1 routing): still
-// bound by streaming the weights, but 64-row tiles would re-read them several times through L2.
-// 128-row tiles, 128-byte rows per step, 4-stage ring (128 KB).
-hipError_t launch_expert_up_bf16_mid(const bf16_t* x_perm, const int32_t* offsets,
-                                     const bf16_t* wg, const bf16_t* wu, int n_rows, int d, int f,
-                                     int E, bf16_t* h, hipStream_t s, const int32_t* row_src,
-                                     int topk) {
-    return launch_pipe<PipeCfg<128, 128, 64, 4, 2, 2, true>>(x_perm, offsets, wg, wu, n_rows, E, f,
-                                                             d, h, s, row_src, topk);
-}
-
+// In between (tens to a few hundred rows per expert, e.g. 16 experts with top-1 routing), down
+// projection: still bound by streaming the weights, but 64-row tiles would re-read them several
+// times through L2.  128-row tiles, 128-byte rows per step, 4-stage ring (128 KB).
 hipError_t launch_expert_down_bf16_mid(const bf16_t* h, const int32_t* offsets, const bf16_t* wd,
                                        int n_rows, int d, int f, int E, bf16_t* y,
                                        hipStream_t s) {

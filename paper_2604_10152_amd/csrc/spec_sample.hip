@@ -35,7 +35,7 @@ __device__ __forceinline__ double wave_scan_incl(double v, int lane) {
 }
 
 // One workgroup per sequence.  The draw needs the smallest id whose running weight exceeds
-// u * total: wave w sums the 256-id tiles w, w+4, ... (coalesced 16-byte loads, butterfly sum,
+// u * total: wave w of the 16 sums the 256-id tiles w, w+16, ... (coalesced 16-byte loads, butterfly sum,
 // fp64) into LDS, every thread walks the tile sums to find the tile where the threshold is
 // crossed, and one wave scans that tile.  Only the order of the fp64 additions differs from a
 // sequential running sum.

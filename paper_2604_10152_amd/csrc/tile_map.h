@@ -20,8 +20,8 @@ struct TileLoc {
 };
 
 // Even split: an expert with M rows gets ceil(M / BM_MAX) m-tiles of equal height (rounded up
-// to the row granule of the matrix instruction in use: 32 or 16), so no tile is a thin remainder that would stream a whole
-// weight tile for a handful of rows.
+// to the row granule of the matrix instruction in use, 32 or 16), so no tile is a thin
+// remainder that would stream a whole weight tile for a handful of rows.
 struct EvenSplit {
     int mt;    // m-tiles of the expert
     int rpt;   // rows per tile (multiple of GRAN, <= BM_MAX); the last tile may hold fewer
