@@ -125,6 +125,43 @@ int moe_expert_up_swiglu_gather(const void* x, const int32_t* row_src, int T, in
                                 const void* w_up, int n_rows, int d_model, int d_ff, int E,
                                 int dtype, void* h, void* stream);
 
+/* Tile-packed operands for the large-batch regime (Sec. 2.2: verification brings hundreds of
+ * rows per expert, the expert GEMMs are then bound by the rate at which L2 serves requests;
+ * packed operands turn sixteen 64-byte requests into eight 128-byte ones).
+ * Layout of a tile-packed bf16 matrix [R, K] (R % 16 == 0, K % 32 == 0; same size as row-major):
+ * 1 KB blocks of 16 rows x 32 columns, block (rb, kb) at byte offset (rb * (K/32) + kb) * 1024;
+ * inside a block the 16-byte chunk c (columns 8c..8c+7 of the block) of row r is piece number
+ * 4*r + (c ^ ((r/2) % 4)).
+ *   moe_pack_weights: w [E, n_rows, n_cols] row-major -> w_packed (same shape, every expert's
+ *     matrix tile-packed); out of place, w_packed must not overlap w.  One-time work: the
+ *     paper's experts are fixed during inference (Sec. 2.1).  bf16 only; n_rows % 16 == 0,
+ *     n_cols % 32 == 0.
+ *   moe_packed_h_bytes: size of the tile-packed intermediate h for n_rows rows (every expert's
+ *     rows padded to whole 16-row blocks: at most n_rows + 16*E rows).
+ *   moe_expert_up_swiglu_gather_packed: as moe_expert_up_swiglu_gather (row_src == NULL: x is
+ *     x_perm [n_rows, d_model]) with w_gate / w_up tile-packed; writes h tile-packed: row r of
+ *     expert e (r counted from expert_offsets[e]) is row 16 * B_e + r of the packed matrix,
+ *     B_e = sum over e' < e of ceil(rows(e') / 16); padding rows are written as zeros.
+ *     x_packed_workspace (may be NULL): moe_packed_h_bytes(n_rows, d_model, E) bytes of scratch;
+ *     if given, the token rows are first gathered into it in the same tile-packed row numbering
+ *     (one extra pass over x) so that the activation loads are 1 KB pieces as well.
+ *   moe_expert_down_packed: as moe_expert_down with h and w_down tile-packed; y_perm row-major.
+ * Results are identical to the row-major entry points' large-batch kernels (same arithmetic in
+ * the same order).  These calls run the large-batch kernel whatever n_rows is; callers with few
+ * rows per expert should use the row-major entry points.  bf16 only. */
+int moe_pack_weights(const void* w, int E, int n_rows, int n_cols, int dtype, void* w_packed,
+                     void* stream);
+size_t moe_packed_h_bytes(int n_rows, int d_ff, int E);
+int moe_expert_up_swiglu_gather_packed(const void* x, const int32_t* row_src, int T, int k,
+                                       const int32_t* expert_offsets, const void* w_gate_packed,
+                                       const void* w_up_packed, int n_rows, int d_model, int d_ff,
+                                       int E, int dtype, void* h_packed, size_t h_packed_bytes,
+                                       void* x_packed_workspace, size_t x_packed_workspace_bytes,
+                                       void* stream);
+int moe_expert_down_packed(const void* h_packed, const int32_t* expert_offsets,
+                           const void* w_down_packed, int n_rows, int d_model, int d_ff, int E,
+                           int dtype, void* y_perm, void* stream);
+
 /* Gate-weighted mix of the selected experts' outputs (Sec. 2.1, Fig. 1b):
  *   out[t] = (residual ? residual[t] : 0) + sum_{s<k} topk_w[t,s] * y_perm[row_of[t*k+s]]
  * accumulated in fp32 in slot order, rounded once to `dtype`.  residual [T,d_model] in

@@ -17,7 +17,8 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "moe_route_topk", "moe_permute", "moe_grouped_swiglu_workspace_bytes", "moe_grouped_swiglu",
-    "moe_grouped_swiglu_static",
+    "moe_grouped_swiglu_static", "moe_pack_weights", "moe_packed_h_bytes",
+    "moe_expert_up_swiglu_gather_packed", "moe_expert_down_packed",
     "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down", "moe_combine", "spec_accept", "moe_hot_experts", "moe_rmsnorm", "specmoe_status_string", "specmoe_abi_version",
     "moe_affinity_table_workspace_bytes", "moe_affinity_table", "moe_nearest_draft_expert",
     "moe_route_topk_draft", "spec_accept_sample", "spec_greedy_tokens", "moe_active_expert_bytes",
@@ -57,6 +58,12 @@ def load_library(build_if_missing: bool = True):
     lib.moe_grouped_swiglu.argtypes = [vp, ip, vp, vp, vp, i, i, i, i, i, vp, vp, sz, vp]
     lib.moe_grouped_swiglu_static.argtypes = [vp, ip, vp, vp, vp, i, i, i, i, i, vp, vp]
     lib.moe_expert_up_swiglu.argtypes = [vp, ip, vp, vp, i, i, i, i, i, vp, vp]
+    lib.moe_pack_weights.argtypes = [vp, i, i, i, i, vp, vp]
+    lib.moe_packed_h_bytes.argtypes = [i, i, i]
+    lib.moe_packed_h_bytes.restype = sz
+    lib.moe_expert_up_swiglu_gather_packed.argtypes = [vp, ip, i, i, ip, vp, vp, i, i, i, i, i, vp, sz,
+                                                       vp, sz, vp]
+    lib.moe_expert_down_packed.argtypes = [vp, ip, vp, i, i, i, i, i, vp, vp]
     lib.moe_expert_up_swiglu_gather.argtypes = [vp, ip, i, i, ip, vp, vp, i, i, i, i, i, vp, vp]
     lib.moe_expert_down.argtypes = [vp, ip, vp, i, i, i, i, i, vp, vp]
     lib.moe_combine.argtypes = [vp, ip, fp, vp, i, i, i, i, vp, vp]
@@ -75,7 +82,9 @@ def load_library(build_if_missing: bool = True):
     lib.specmoe_status_string.restype = ctypes.c_char_p
     lib.specmoe_abi_version.restype = i
     for name in ("moe_route_topk", "moe_permute", "moe_grouped_swiglu", "moe_combine",
-                 "moe_grouped_swiglu_static",
+                 "moe_grouped_swiglu_static", "moe_pack_weights",
+                 "moe_expert_up_swiglu_gather_packed", "moe_expert_down_packed", "moe_pack_weights", "moe_packed_h_bytes",
+    "moe_expert_up_swiglu_gather_packed", "moe_expert_down_packed",
                  "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down",
                  "moe_hot_experts", "moe_affinity_table", "moe_nearest_draft_expert",
                  "moe_route_topk_draft", "spec_accept_sample", "spec_greedy_tokens",
@@ -188,6 +197,42 @@ def moe_expert_up_swiglu_gather(x, row_src, k, expert_offsets, w_gate, w_up, h, 
         _ptr(expert_offsets, torch.int32, "expert_offsets"), _ptr(w_gate, x.dtype, "w_gate"),
         _ptr(w_up, x.dtype, "w_up"), n_rows, d, f, E, _dtype_code(x), _ptr(h, x.dtype, "h"),
         _stream(stream)), "moe_expert_up_swiglu_gather")
+
+
+def moe_pack_weights(w, w_packed, stream=None):
+    E, rows, cols = w.shape
+    _check(load_library().moe_pack_weights(
+        _ptr(w, torch.bfloat16, "w"), E, rows, cols, BF16, _ptr(w_packed, torch.bfloat16, "w_packed"),
+        _stream(stream)), "moe_pack_weights")
+
+
+def moe_packed_h_bytes(n_rows, d_ff, E) -> int:
+    return int(load_library().moe_packed_h_bytes(n_rows, d_ff, E))
+
+
+def moe_expert_up_swiglu_gather_packed(x, row_src, k, expert_offsets, w_gate_packed, w_up_packed,
+                                       n_rows, h_packed, x_packed_workspace=None, stream=None):
+    T, d = x.shape
+    E, f, _ = w_gate_packed.shape
+    _check(load_library().moe_expert_up_swiglu_gather_packed(
+        _ptr(x, torch.bfloat16, "x"), _ptr(row_src, torch.int32, "row_src"), T, k,
+        _ptr(expert_offsets, torch.int32, "expert_offsets"),
+        _ptr(w_gate_packed, torch.bfloat16, "w_gate_packed"),
+        _ptr(w_up_packed, torch.bfloat16, "w_up_packed"), n_rows, d, f, E, BF16,
+        _ptr(h_packed, name="h_packed"), h_packed.numel() * h_packed.element_size(),
+        _ptr(x_packed_workspace, name="x_packed_workspace"),
+        0 if x_packed_workspace is None else
+        x_packed_workspace.numel() * x_packed_workspace.element_size(),
+        _stream(stream)), "moe_expert_up_swiglu_gather_packed")
+
+
+def moe_expert_down_packed(h_packed, expert_offsets, w_down_packed, y_perm, stream=None):
+    n_rows, d = y_perm.shape
+    E, _, f = w_down_packed.shape
+    _check(load_library().moe_expert_down_packed(
+        _ptr(h_packed, name="h_packed"), _ptr(expert_offsets, torch.int32, "expert_offsets"),
+        _ptr(w_down_packed, torch.bfloat16, "w_down_packed"), n_rows, d, f, E, BF16,
+        _ptr(y_perm, torch.bfloat16, "y_perm"), _stream(stream)), "moe_expert_down_packed")
 
 
 def moe_expert_down(h, expert_offsets, w_down, y_perm, stream=None):

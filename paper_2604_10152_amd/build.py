@@ -13,7 +13,7 @@ PEAKS_LIB = os.path.join(HERE, "libspecmoe_peaks.so")     # measurement helpers 
 PEAKS_SOURCES = ["peaks.hip"]
 SOURCES = ["api.hip", "route_topk.hip", "permute.hip", "grouped_swiglu_f32.hip",
            "grouped_swiglu_bf16.hip", "grouped_gemm_bf16_pipe.hip", "grouped_gemm_bf16_pipe16.hip", "combine.hip", "spec_accept.hip", "hot_experts.hip",
-           "draft_route.hip", "spec_sample.hip"]
+           "draft_route.hip", "spec_sample.hip", "pack.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

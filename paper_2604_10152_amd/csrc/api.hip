@@ -133,6 +133,80 @@ int moe_grouped_swiglu(const void* x_perm, const int32_t* expert_offsets, const 
                            y_perm, stream);
 }
 
+int moe_pack_weights(const void* w, int E, int n_rows, int n_cols, int dtype, void* w_packed,
+                     void* stream) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (dtype != SPECMOE_BF16) return SPECMOE_ERR_DTYPE;
+    if (E < 1 || E > SPECMOE_MAX_EXPERTS || n_rows < 16 || n_cols < 32 || n_rows % 16 != 0 ||
+        n_cols % 32 != 0)
+        return SPECMOE_ERR_SHAPE;
+    if (!w || !w_packed) return SPECMOE_ERR_NULL;
+    const size_t bytes = (size_t)E * n_rows * n_cols * 2;
+    const uintptr_t a = (uintptr_t)w, b = (uintptr_t)w_packed;
+    if (((a | b) & 15u) != 0 || (a < b + bytes && b < a + bytes)) return SPECMOE_ERR_SHAPE;
+    return dev(launch_pack_tiles((const bf16_t*)w, (long long)E * n_rows, n_cols,
+                                 (bf16_t*)w_packed, (hipStream_t)stream));
+}
+
+size_t moe_packed_h_bytes(int n_rows, int d_ff, int E) {
+    if (n_rows < 0 || d_ff < 1 || E < 1) return 0;
+    return ((size_t)(n_rows / 16) + (size_t)E) * 16 * (size_t)d_ff * 2;
+}
+
+int moe_expert_up_swiglu_gather_packed(const void* x, const int32_t* row_src, int T, int k,
+                                       const int32_t* expert_offsets, const void* w_gate_packed,
+                                       const void* w_up_packed, int n_rows, int d_model, int d_ff,
+                                       int E, int dtype, void* h_packed, size_t h_packed_bytes,
+                                       void* x_packed_workspace, size_t x_packed_workspace_bytes,
+                                       void* stream) {
+    const int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
+    if (st != SPECMOE_OK) return st;
+    if (dtype != SPECMOE_BF16) return SPECMOE_ERR_DTYPE;
+    if (row_src) {
+        if (T < 0 || k < 1 || k > SPECMOE_MAX_TOPK || pairs_overflow(T, k) ||
+            (long long)n_rows > (long long)T * k)
+            return SPECMOE_ERR_SHAPE;
+        if ((unsigned long long)T * (unsigned long long)d_model * 2 >= (1ull << 32))
+            return SPECMOE_ERR_SHAPE;
+    }
+    if (n_rows == 0) return SPECMOE_OK;
+    if (!x || !expert_offsets || !w_gate_packed || !w_up_packed || !h_packed)
+        return SPECMOE_ERR_NULL;
+    if (h_packed_bytes < moe_packed_h_bytes(n_rows, d_ff, E) || ((uintptr_t)h_packed & 15u) != 0)
+        return SPECMOE_ERR_WORKSPACE;
+    if (x_packed_workspace) {
+        if (x_packed_workspace_bytes < moe_packed_h_bytes(n_rows, d_model, E) ||
+            ((uintptr_t)x_packed_workspace & 15u) != 0 || ((uintptr_t)x & 15u) != 0)
+            return SPECMOE_ERR_WORKSPACE;
+        const hipError_t e = launch_gather_pack_rows(
+            (const bf16_t*)x, row_src, row_src ? k : 1, expert_offsets, n_rows, E, d_model,
+            (bf16_t*)x_packed_workspace, (hipStream_t)stream);
+        if (e != hipSuccess) return SPECMOE_ERR_DEVICE;
+        return dev(launch_expert_up_bf16_packed_x(
+            (const bf16_t*)x_packed_workspace, expert_offsets, (const bf16_t*)w_gate_packed,
+            (const bf16_t*)w_up_packed, n_rows, d_model, d_ff, E, (bf16_t*)h_packed,
+            (hipStream_t)stream));
+    }
+    return dev(launch_expert_up_bf16_packed((const bf16_t*)x, expert_offsets,
+                                            (const bf16_t*)w_gate_packed,
+                                            (const bf16_t*)w_up_packed, n_rows, d_model, d_ff, E,
+                                            (bf16_t*)h_packed, (hipStream_t)stream, row_src,
+                                            row_src ? k : 1));
+}
+
+int moe_expert_down_packed(const void* h_packed, const int32_t* expert_offsets,
+                           const void* w_down_packed, int n_rows, int d_model, int d_ff, int E,
+                           int dtype, void* y_perm, void* stream) {
+    const int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
+    if (st != SPECMOE_OK) return st;
+    if (dtype != SPECMOE_BF16) return SPECMOE_ERR_DTYPE;
+    if (n_rows == 0) return SPECMOE_OK;
+    if (!h_packed || !expert_offsets || !w_down_packed || !y_perm) return SPECMOE_ERR_NULL;
+    return dev(launch_expert_down_bf16_packed((const bf16_t*)h_packed, expert_offsets,
+                                              (const bf16_t*)w_down_packed, n_rows, d_model, d_ff,
+                                              E, (bf16_t*)y_perm, (hipStream_t)stream));
+}
+
 // Scratch of moe_grouped_swiglu_static: one copy per GPU, held until the process ends.
 static __device__ __align__(256) unsigned char scratch[SPECMOE_STATIC_SCRATCH_BYTES];
 
@@ -304,6 +378,6 @@ const char* specmoe_status_string(int status) {
     }
 }
 
-int specmoe_abi_version(void) { return 5; }
+int specmoe_abi_version(void) { return 7; }
 
 }  // extern "C"

@@ -78,6 +78,21 @@ hipError_t launch_expert_up_bf16_large16(const bf16_t* x_perm, const int32_t* of
 hipError_t launch_expert_down_bf16_large16(const bf16_t* h, const int32_t* offsets,
                                            const bf16_t* wd, int n_rows, int d, int f, int E,
                                            bf16_t* y, hipStream_t s);
+hipError_t launch_expert_up_bf16_packed(const bf16_t* x, const int32_t* offsets,
+                                        const bf16_t* wg_packed, const bf16_t* wu_packed,
+                                        int n_rows, int d, int f, int E, bf16_t* h_packed,
+                                        hipStream_t s, const int32_t* row_src, int topk);
+hipError_t launch_expert_down_bf16_packed(const bf16_t* h_packed, const int32_t* offsets,
+                                          const bf16_t* wd_packed, int n_rows, int d, int f,
+                                          int E, bf16_t* y, hipStream_t s);
+hipError_t launch_expert_up_bf16_packed_x(const bf16_t* x_packed, const int32_t* offsets,
+                                          const bf16_t* wg_packed, const bf16_t* wu_packed,
+                                          int n_rows, int d, int f, int E, bf16_t* h_packed,
+                                          hipStream_t s);
+hipError_t launch_gather_pack_rows(const bf16_t* x, const int32_t* row_src, int topk,
+                                   const int32_t* offsets, int n_rows, int E, int K,
+                                   bf16_t* dst, hipStream_t s);
+hipError_t launch_pack_tiles(const bf16_t* src, long long rows, int K, bf16_t* dst, hipStream_t s);
 hipError_t launch_expert_up_bf16_small(const bf16_t* x_perm, const int32_t* offsets,
                                        const bf16_t* wg, const bf16_t* wu, int n_rows, int d,
                                        int f, int E, bf16_t* h, hipStream_t s,

@@ -49,6 +49,14 @@ __device__ __forceinline__ int swz(int r, int c) {
     return r * C::ROW_BYTES + ((c ^ ((r / C::RPG) % C::CHUNKS)) << 4);
 }
 
+// Tile-packed matrix [R rows, K columns] of bf16 (R % 16 == 0, K % 32 == 0), same size as the
+// row-major one: 1 KB blocks of 16 rows x 32 columns; block (rb, kb) at byte offset
+// (rb * (K / 32) + kb) * 1024, i.e. row block rb starts at element rb * 16 * K.  A block holds
+// the LDS image of its piece under swz<> with 64-byte rows: the 16-byte chunk c (8 columns) of
+// row r sits at piece index 4 * r + (c ^ ((r / 2) % 4)).  A wave-load of such a block is 1 KB
+// of consecutive memory and lands in LDS ready for the fragment reads.
+constexpr int kPackRows = 16, kPackCols = 32;
+
 // Row pitch of the LDS image of a SwiGLU output tile (128 bf16 columns + 16 bytes of padding
 // so that the 8-byte accumulator stores of 32 consecutive rows spread over the banks).
 constexpr int kStageRowBytes = 128 * 2 + 16;

@@ -17,6 +17,8 @@ struct TileLoc {
     int row0;        // first row of the tile in the permuted row space
     int tile_rows;   // valid rows in the tile (1 .. BM)
     int nt;          // n-tile index
+    int blk0;        // 16-row blocks in front of the tile when every expert's rows are padded to
+                     // a whole number of blocks (row numbering of the tile-packed matrices)
 };
 
 // Even split: an expert with M rows gets ceil(M / BM_MAX) m-tiles of equal height (rounded up
@@ -72,16 +74,19 @@ __device__ __forceinline__ bool locate_tile_impl(const int32_t* __restrict__ off
     const long long L = (long long)(block_id % kXcds) * per_xcd + slot;
     if (slot >= per_xcd || L >= G) return false;
     int base_mt = 0;                              // m-tiles of the experts before this sweep
-    int expert = -1, row0 = 0, rows = 0, nt = 0;
+    int base_blk = 0;                             // 16-row blocks of the experts before this sweep
+    int expert = -1, row0 = 0, rows = 0, nt = 0, blk0 = 0;
     for (int e0 = 0; e0 < E && expert < 0; e0 += kWave) {
         const int e = e0 + lane;
         const int lo = e < E ? offsets[e] : 0, hi = e < E ? offsets[e + 1] : 0;
         const EvenSplit sp = Split::of(hi - lo);
-        int incl = sp.mt;                         // inclusive scan of mt over the lanes
+        const int nblk = (hi - lo + 15) / 16;
+        int incl = sp.mt, incl_blk = nblk;        // inclusive scans over the lanes
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
             const int v = __shfl_up(incl, off, kWave);
-            if (lane >= off) incl += v;
+            const int vb = __shfl_up(incl_blk, off, kWave);
+            if (lane >= off) { incl += v; incl_blk += vb; }
         }
         const long long end = (long long)(base_mt + incl) * NT;      // tiles up to and incl. e
         const unsigned long long hit = __ballot(sp.mt > 0 && L < end);
@@ -96,14 +101,18 @@ __device__ __forceinline__ bool locate_tile_impl(const int32_t* __restrict__ off
             expert = e0 + src;
             row0 = lo_s + mi * rpt;
             rows = min(rpt, hi_s - row0);
+            blk0 = base_blk + __shfl(incl_blk, src, kWave) - __shfl(nblk, src, kWave) +
+                   mi * rpt / 16;                 // tile heights are multiples of 16
         }
         base_mt += __shfl(incl, kWave - 1, kWave);
+        base_blk += __shfl(incl_blk, kWave - 1, kWave);
     }
     // the values are the same in every lane; say so to the compiler (scalar registers)
     t.expert = __builtin_amdgcn_readfirstlane(expert);
     t.row0 = __builtin_amdgcn_readfirstlane(row0);
     t.tile_rows = __builtin_amdgcn_readfirstlane(rows);
     t.nt = __builtin_amdgcn_readfirstlane(nt);
+    t.blk0 = __builtin_amdgcn_readfirstlane(blk0);
     return t.expert >= 0;
 }
 

@@ -14,11 +14,12 @@ class MoEVerifyLayer:
     """
 
     def __init__(self, T, d_model, d_ff, E, k, dtype, device="cuda", renorm=True,
-                 fuse_gather=True):
+                 fuse_gather=True, pack_x=True):
         """fuse_gather: moe_permute writes indices only and the gate/up GEMM gathers token rows
         itself (moe_expert_up_swiglu_gather); False materialises x_perm first."""
         self.T, self.d, self.f, self.E, self.k = T, d_model, d_ff, E, k
         self.dtype, self.renorm = dtype, renorm
+        self.pack_x = pack_x       # packed path: gather the token rows into tile-packed form first
         self.fuse_gather = fuse_gather and T * d_model * (4 if dtype == torch.float32 else 2) < 2 ** 32
         P = T * k
         dev = torch.device(device)
@@ -32,16 +33,37 @@ class MoEVerifyLayer:
         self.y_perm = torch.empty((P, d_model), dtype=dtype, device=dev)
         self.out = torch.empty((T, d_model), dtype=dtype, device=dev)
         self.h = torch.empty((P, d_ff), dtype=dtype, device=dev)
+        self.h_packed = None                     # allocated on first use of packed weights
+        self.x_packed = None
+
+    # rows per expert (average) from which the tile-packed large-batch path pays off
+    PACKED_MIN_ROWS_PER_EXPERT = 192
+
+    @staticmethod
+    def pack_weights(w_gate, w_up, w_down, stream=None):
+        """One-time re-layout of the expert weights for the large-batch path (bf16 only):
+        returns the dict to pass as `packed=` to forward().  The row-major tensors stay valid and
+        are still used whenever a batch is too small for that path."""
+        out = {}
+        for name, w in (("w_gate", w_gate), ("w_up", w_up), ("w_down", w_down)):
+            wp = torch.empty_like(w)
+            B.moe_pack_weights(w, wp, stream)
+            out[name] = wp
+        return out
 
     def forward(self, x, w_router, w_gate, w_up, w_down, bias=None, residual=None, out=None,
-                stream=None, marks=None, draft_remap=None):
+                stream=None, marks=None, draft_remap=None, packed=None):
         """Enqueues the layer.  `marks`, if given, is a sequence of six torch events recorded on
         `stream` before the router and after each of the five calls (route, permute, gate/up,
         down, combine): the benchmark's per-kernel times.
         `draft_remap` ([E] int32 from moe_nearest_draft_expert) switches to the draft model's
         routing: selected experts that are not resident are replaced by their nearest draft
-        expert, so only draft experts compute."""
+        expert, so only draft experts compute.
+        `packed` (from pack_weights) switches the two expert GEMMs to the tile-packed entry points
+        when the batch is large enough (bf16, at least 192 rows per expert on average)."""
         out = self.out if out is None else out
+        use_packed = (packed is not None and self.dtype == torch.bfloat16 and self.fuse_gather and
+                      self.T * self.k >= self.PACKED_MIN_ROWS_PER_EXPERT * self.E)
         if marks is not None:
             marks[0].record(stream)
         if draft_remap is None:
@@ -56,14 +78,30 @@ class MoEVerifyLayer:
                       self.expert_offsets, self.row_src, self.row_of, stream)
         if marks is not None:
             marks[2].record(stream)
-        if self.fuse_gather:
+        if use_packed:
+            if self.h_packed is None:
+                self.h_packed = torch.empty(
+                    (B.moe_packed_h_bytes(self.T * self.k, self.f, self.E),), dtype=torch.uint8,
+                    device=self.h.device)
+                self.x_packed = torch.empty(
+                    (B.moe_packed_h_bytes(self.T * self.k, self.d, self.E),), dtype=torch.uint8,
+                    device=self.h.device)
+            B.moe_expert_up_swiglu_gather_packed(x, self.row_src, self.k, self.expert_offsets,
+                                                 packed["w_gate"], packed["w_up"],
+                                                 self.T * self.k, self.h_packed,
+                                                 self.x_packed if self.pack_x else None, stream)
+        elif self.fuse_gather:
             B.moe_expert_up_swiglu_gather(x, self.row_src, self.k, self.expert_offsets, w_gate,
                                           w_up, self.h, stream)
         else:
             B.moe_expert_up_swiglu(self.x_perm, self.expert_offsets, w_gate, w_up, self.h, stream)
         if marks is not None:
             marks[3].record(stream)
-        B.moe_expert_down(self.h, self.expert_offsets, w_down, self.y_perm, stream)
+        if use_packed:
+            B.moe_expert_down_packed(self.h_packed, self.expert_offsets, packed["w_down"],
+                                     self.y_perm, stream)
+        else:
+            B.moe_expert_down(self.h, self.expert_offsets, w_down, self.y_perm, stream)
         if marks is not None:
             marks[4].record(stream)
         B.moe_combine(self.y_perm, self.row_of, self.topk_w, residual, out, stream)

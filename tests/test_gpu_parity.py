@@ -597,3 +597,85 @@ def test_zero_sizes_and_single_hot_expert():
         want = orc.moe_layer_brute_force(f64(x), f64(wr), f64(wg), f64(wu), f64(wd), 1, f64(bias), True)
         assert (layer.topk_idx.cpu().numpy() == 2).all()
         check_float(f64(out), want, dtype, "one hot expert")
+
+
+# ------------------------------------------------------------------ tile-packed operands
+def _tile_packed(w):
+    """The packed layout written out from its definition (test side): 1 KB blocks of 16 rows x 32
+    columns, block (rb, kb) at (rb * K/32 + kb), chunk c of row r at piece 4r + (c ^ ((r/2)%4))."""
+    a = w.view(torch.int16).cpu().numpy()
+    E, R, K = a.shape
+    out = np.empty_like(a).reshape(E, R // 16, K // 32, 64, 8)
+    blocks = a.reshape(E, R // 16, 16, K // 32, 4, 8)            # [E, rb, r, kb, c, 8]
+    for r in range(16):
+        for c in range(4):
+            out[:, :, :, 4 * r + (c ^ ((r // 2) % 4)), :] = blocks[:, :, r, :, c, :]
+    return out.reshape(E, R, K)
+
+
+@pytest.mark.parametrize("E,R,K", [(3, 64, 96), (2, 384, 256), (1, 16, 32)])
+def test_pack_weights_layout(E, R, K):
+    _say(f"pack weights {E}x{R}x{K}")
+    g = torch.Generator().manual_seed(R + K)
+    w = torch.randn(E, R, K, generator=g).to(torch.bfloat16).cuda()
+    wp = torch.full_like(w, float("nan"))
+    sm.moe_pack_weights(w, wp)
+    torch.cuda.synchronize()
+    assert (wp.view(torch.int16).cpu().numpy() == _tile_packed(w)).all()
+
+
+@pytest.mark.parametrize("d,f,rows", [
+    (256, 384, [300, 0, 37, 1, 513, 256, 330]),      # full, ragged, empty experts; padded blocks
+    (512, 1408, [700, 650]),
+    (256, 384, [3, 0, 70, 1, 129, 64, 0, 0]),        # few rows: still correct on the packed path
+    (64, 64, [1]),
+])
+def test_packed_expert_gemms(d, f, rows):
+    """moe_expert_up_swiglu_gather_packed + moe_expert_down_packed against the oracle, and - where
+    the row-major entry points pick the same large-batch kernel - bit for bit against them."""
+    _say(f"packed expert GEMMs d={d} f={f} rows={rows}")
+    E = len(rows)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    n = int(off[-1])
+    g = torch.Generator().manual_seed(d + f + n)
+    xp = (torch.randn(n, d, generator=g) / d ** 0.5).to(torch.bfloat16)
+    wg = (torch.randn(E, f, d, generator=g) * 0.5).to(torch.bfloat16)
+    wu = (torch.randn(E, f, d, generator=g) * 0.5).to(torch.bfloat16)
+    wd = (torch.randn(E, d, f, generator=g) * (0.5 / f ** 0.5)).to(torch.bfloat16)
+    doff = dev(torch.from_numpy(off))
+    pk = sm.MoEVerifyLayer.pack_weights(dev(wg), dev(wu), dev(wd))
+    hp = torch.full((sm.moe_packed_h_bytes(n, f, E),), 0xff, dtype=torch.uint8, device="cuda")
+    y = torch.full((n, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    sm.moe_expert_up_swiglu_gather_packed(dev(xp), None, 1, doff, pk["w_gate"], pk["w_up"], n, hp)
+    sm.moe_expert_down_packed(hp, doff, pk["w_down"], y)
+    # the same with the activation rows gathered into tile-packed form first: identical bits
+    hp2 = torch.full_like(hp, 0xee)
+    xws = torch.full((sm.moe_packed_h_bytes(n, d, E),), 0xdd, dtype=torch.uint8, device="cuda")
+    y3 = torch.full_like(y, float("nan"))
+    sm.moe_expert_up_swiglu_gather_packed(dev(xp), None, 1, doff, pk["w_gate"], pk["w_up"], n, hp2, xws)
+    sm.moe_expert_down_packed(hp2, doff, pk["w_down"], y3)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y3.view(torch.int16))
+    used = (sum((r + 15) // 16 for r in rows)) * 16 * f * 2          # blocks the batch really uses
+    assert torch.equal(hp[:used], hp2[:used])
+    ey = orc.grouped_swiglu(f64(xp), off, LazyF64(wg), LazyF64(wu), LazyF64(wd))
+    check_float(f64(y), ey, torch.bfloat16, f"packed rows={rows}")
+    if n >= 192 * E:
+        y2 = _gpu_grouped(xp, torch.from_numpy(off), wg, wu, wd)
+        assert torch.equal(y.cpu().view(torch.int16), y2.view(torch.int16))
+
+
+def test_layer_cfg4_packed_path():
+    """The benchmark workload on the tile-packed path: same routing, output bit-identical to the
+    row-major path (same kernels' arithmetic in the same order)."""
+    cfg = synth.CONFIGS[4]
+    _say("layer cfg4 packed")
+    L = synth.make_layer(cfg, "cuda", seed=4)
+    layer, out = _run_layer(cfg, L)
+    ref = out.clone()
+    pk = sm.MoEVerifyLayer.pack_weights(L["w_gate"], L["w_up"], L["w_down"])
+    out2 = layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
+                         packed=pk)
+    torch.cuda.synchronize()
+    assert layer.h_packed is not None
+    assert torch.equal(ref.view(torch.int16), out2.view(torch.int16))

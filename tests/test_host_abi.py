@@ -29,7 +29,7 @@ def test_header_and_library_agree(lib):
     assert set(declared) == set(binding.EXPORTED_SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.specmoe_abi_version() == 5
+    assert lib.specmoe_abi_version() == 7
 
 
 def test_status_strings(lib):
@@ -59,6 +59,24 @@ def test_static_scratch_validation(lib):
     assert f(P, P, P, P, P, 8193, 64, 1024, 2, 1, P, N) == 4             # beyond the 16 MiB scratch
     assert f(P, P, P, P, P, 4097, 64, 1024, 2, 0, P, N) == 4             # same, fp32
     assert f(P, P, P, P, P, 0, 64, 64, 2, 1, P, N) == 0                  # nothing to do
+
+
+def test_packed_entry_points_validation(lib):
+    pw, hb = lib.moe_pack_weights, lib.moe_packed_h_bytes
+    assert pw(P, 2, 64, 64, 0, ctypes.c_void_p(0x100000), N) == 3        # fp32 is not packed
+    assert pw(P, 2, 60, 64, 1, ctypes.c_void_p(0x100000), N) == 2        # rows % 16
+    assert pw(P, 2, 64, 48, 1, ctypes.c_void_p(0x100000), N) == 2        # cols % 32
+    assert pw(P, 2, 64, 64, 1, P, N) == 2                                # in place
+    assert pw(N, 2, 64, 64, 1, P, N) == 1
+    assert hb(4096, 14336, 8) == (4096 // 16 + 8) * 16 * 14336 * 2
+    assert hb(-1, 64, 1) == 0
+    up, down = lib.moe_expert_up_swiglu_gather_packed, lib.moe_expert_down_packed
+    assert up(P, N, 0, 1, P, P, P, 64, 64, 64, 2, 0, P, 1 << 30, N, 0, N) == 3  # bf16 only
+    assert up(P, N, 0, 1, P, P, P, 64, 64, 64, 2, 1, P, 16, N, 0, N) == 4       # h too small
+    assert up(P, P, 8, 2, P, P, P, 64, 64, 64, 2, 1, P, 1 << 30, N, 0, N) == 2  # n_rows > T*k
+    assert up(P, N, 0, 1, P, P, P, 64, 64, 64, 2, 1, P, 1 << 30, P, 16, N) == 4  # x workspace too small
+    assert down(P, P, P, 64, 64, 64, 2, 0, P, N) == 3
+    assert down(N, P, P, 64, 64, 64, 2, 1, P, N) == 1
 
 
 def test_route_validation(lib):
