@@ -151,7 +151,7 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
         wait_vmcnt<0>();                           // no load may outlive the workgroup's LDS
 
         const int mrow = lane & 15, cq = (lane >> 4) * 4;
-        if (C::SWIGLU) __builtin_amdgcn_s_barrier();   // every wave's loads have landed
+        if (C::SWIGLU && !PO) __builtin_amdgcn_s_barrier();   // every wave's loads have landed
 #pragma unroll
         for (int i = 0; i < TA; ++i) {
             const int trow = 16 * (wm + C::WM * i) + mrow;
@@ -172,7 +172,23 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
                     }
                 }
                 const uint2 pk = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-                if (C::SWIGLU) {
+                if (C::SWIGLU && PO) {
+                    // tile-packed h straight from the registers: the wave's sub-tile j is the
+                    // column half j of the 32-column block wn of row block (wm + WM*i); this
+                    // lane holds half a 16-byte chunk.  Rows beyond the tile's last row (padding
+                    // of the expert's last block) are written as zeros.
+                    static_assert(!PO || (TN16 == 4 && C::BN_OUT == 128), "packed output tiling");
+                    const int col0 = n0 + 32 * wn;
+                    if (col0 < N) {
+                        const int chunk = 2 * j + (cq >> 3);
+                        const int piece = 4 * mrow + (chunk ^ ((mrow >> 1) & 3));
+                        unsigned char* blk = reinterpret_cast<unsigned char*>(
+                            Cout + ((size_t)(t.blk0 + wm + C::WM * i) * 16 * N +
+                                    (size_t)(col0 / 32) * 512));
+                        *reinterpret_cast<uint2*>(blk + piece * 16 + ((cq >> 2) & 1) * 8) =
+                            trow < tile_rows ? pk : make_uint2(0u, 0u);
+                    }
+                } else if (C::SWIGLU) {
                     *reinterpret_cast<uint2*>(lds_raw + trow * kStageRowBytes + ctile * 2) = pk;
                 } else {
                     const int col = n0 + ctile;
@@ -262,32 +278,12 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
 
     dispatch_count(ta, run_pp, std::make_integer_sequence<int, TM16 + 1>{});
 
-    if (C::SWIGLU) {
+    if (C::SWIGLU && !PO) {
         // cooperative write-out of the staged tile: 16 bytes per lane, whole rows
         static_assert(!C::SWIGLU || (size_t)C::BM * kStageRowBytes <= C::LDS_BYTES, "stage tile");
         static_assert(!C::SWIGLU || C::BN_OUT == 128, "stage row pitch assumes 128 columns");
         __builtin_amdgcn_s_barrier();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (PO) {
-            // tile-packed output: the tile is (row blocks) x (4 column blocks of 32) 1 KB blocks;
-            // piece p of a block is chunk (p%4) ^ ((r/2)%4) of row r = p/4.  Rows beyond the
-            // tile's last row (padding of the expert's last block) are written as zeros.
-            const int nblk = (tile_rows + 15) / 16;
-            for (int g = tid; g < nblk * 256; g += C::THREADS) {
-                const int blk = g >> 6, piece = g & 63;
-                const int rbt = blk >> 2, q = blk & 3;
-                const int r = piece >> 2, c = (piece & 3) ^ ((r >> 1) & 3);
-                const int trow = rbt * 16 + r, col = n0 + q * 32;
-                if (col >= N) continue;
-                U128 v = {0, 0, 0, 0};
-                if (trow < tile_rows)
-                    v = *reinterpret_cast<const U128*>(lds_raw + trow * kStageRowBytes +
-                                                       (q * 32 + c * 8) * 2);
-                bf16_t* dst = Cout + ((size_t)(t.blk0 + rbt) * 16 * N + (size_t)(col / 32) * 512);
-                *reinterpret_cast<U128*>(reinterpret_cast<unsigned char*>(dst) + piece * 16) = v;
-            }
-            return;
-        }
         constexpr int CPR = C::BN_OUT / 8;                  // 16-byte chunks per tile row
         constexpr int RPP = C::THREADS / CPR;               // rows per pass
         const int cr = tid / CPR, cc = tid % CPR;
