@@ -164,16 +164,20 @@ def source_fingerprint():
 KERNELS = ("route", "permute", "up", "down", "combine", "accept")
 
 
-def algorithmic_work(cfg, T, active):
+def algorithmic_work(cfg, T, active, rows_materialised=False):
     """Flops and bytes every kernel of one layer has to do at T tokens (algorithmic: the
-    active experts' weights once, activations and intermediates read and written once)."""
+    active experts' weights once, activations and intermediates read and written once).
+    rows_materialised: the permute step writes the dispatched token rows (tile-packed path);
+    otherwise the gate/up kernel gathers them from the token matrix itself."""
     es = 4 if cfg.dtype == "f32" else 2
     d, f, E, k = cfg.d_model, cfg.d_ff, cfg.E, cfg.k
     P = T * k
+    moved = (T * d + P * d) * es if rows_materialised else 0
+    x_read = P * d if rows_materialised else T * d
     return {
         "route": {"flops": 2.0 * T * d * E, "bytes": (T * d + E * d) * es + P * 8},
-        "permute": {"flops": 0.0, "bytes": P * 4 * 3 + (E + 1) * 4},
-        "up": {"flops": 4.0 * P * d * f, "bytes": (active * 2 * d * f + T * d + P * f) * es},
+        "permute": {"flops": 0.0, "bytes": P * 4 * 3 + (E + 1) * 4 + moved},
+        "up": {"flops": 4.0 * P * d * f, "bytes": (active * 2 * d * f + x_read + P * f) * es},
         "down": {"flops": 2.0 * P * d * f, "bytes": (active * d * f + P * f + P * d) * es},
         "combine": {"flops": 2.0 * P * d, "bytes": (P * d + T * d) * es + P * 8},
         "accept": {"flops": 0.0, "bytes": cfg.B * (2 * cfg.gamma + 2) * 4 * 2},
@@ -231,7 +235,9 @@ class LayerRun:
             whole.append(m[0].elapsed_time(m[6]))
         counts = (self.layer.expert_offsets[1:] - self.layer.expert_offsets[:-1]).cpu()
         active = int((counts > 0).sum())
-        work = algorithmic_work(self.cfg, self.T, active)
+        packed_rows = (self.packed is not None and self.layer.pack_x and
+                       self.T * self.cfg.k >= self.layer.PACKED_MIN_ROWS_PER_EXPERT * self.cfg.E)
+        work = algorithmic_work(self.cfg, self.T, active, rows_materialised=packed_rows)
         kernels = {}
         for n in KERNELS:
             ms = statistics.median(per[n])
@@ -257,7 +263,8 @@ def kernel_name(cfg, T):
     rows = T * cfg.k
     if rows >= 192 * cfg.E:
         return ("grouped_gemm_bf16_pipe16_kernel<PipeCfg<320,256,32,4,2,4,true>> (gate/up + SwiGLU; "
-                "tile-packed weights and h unless --row-major)")
+                "tile-packed operands unless --row-major: the permute step then writes the "
+                "dispatched rows tile-packed)")
     if cfg.d_model >= 4096 and rows >= 48 * cfg.E:
         return "grouped_gemm_bf16_pipe16_kernel<PipeCfg<192,256,32,4,2,4,true>> (gate/up + SwiGLU)"
     if cfg.d_model >= 4096:

@@ -145,6 +145,12 @@ int moe_expert_up_swiglu_gather(const void* x, const int32_t* row_src, int T, in
  *     x_packed_workspace (may be NULL): moe_packed_h_bytes(n_rows, d_model, E) bytes of scratch;
  *     if given, the token rows are first gathered into it in the same tile-packed row numbering
  *     (one extra pass over x) so that the activation loads are 1 KB pieces as well.
+ *   moe_permute_rows_packed / moe_expert_up_swiglu_packed: the two steps of the call above with a
+ *     workspace, as calls of their own (the packed rows are then the caller's buffer: the token
+ *     dispatch of Sec. 2.1 written once in the layout the GEMM loads).  moe_permute_rows_packed
+ *     gathers x[row_src[r] / k] (row_src == NULL: x[r]) into x_packed, row numbering as for h,
+ *     padding rows zero; x 16-byte aligned.  moe_expert_up_swiglu_packed reads such an x_packed.
+ *     x_packed_bytes >= moe_packed_h_bytes(n_rows, d_model, E).
  *   moe_expert_down_packed: as moe_expert_down with h and w_down tile-packed; y_perm row-major.
  * Results are identical to the row-major entry points' large-batch kernels (same arithmetic in
  * the same order).  These calls run the large-batch kernel whatever n_rows is; callers with few
@@ -158,6 +164,13 @@ int moe_expert_up_swiglu_gather_packed(const void* x, const int32_t* row_src, in
                                        int E, int dtype, void* h_packed, size_t h_packed_bytes,
                                        void* x_packed_workspace, size_t x_packed_workspace_bytes,
                                        void* stream);
+int moe_permute_rows_packed(const void* x, const int32_t* row_src, int T, int k,
+                            const int32_t* expert_offsets, int n_rows, int d_model, int E,
+                            int dtype, void* x_packed, size_t x_packed_bytes, void* stream);
+int moe_expert_up_swiglu_packed(const void* x_packed, size_t x_packed_bytes,
+                                const int32_t* expert_offsets, const void* w_gate_packed,
+                                const void* w_up_packed, int n_rows, int d_model, int d_ff, int E,
+                                int dtype, void* h_packed, size_t h_packed_bytes, void* stream);
 int moe_expert_down_packed(const void* h_packed, const int32_t* expert_offsets,
                            const void* w_down_packed, int n_rows, int d_model, int d_ff, int E,
                            int dtype, void* y_perm, void* stream);

@@ -19,6 +19,7 @@ EXPORTED_SYMBOLS = (
     "moe_route_topk", "moe_permute", "moe_grouped_swiglu_workspace_bytes", "moe_grouped_swiglu",
     "moe_grouped_swiglu_static", "moe_pack_weights", "moe_packed_h_bytes",
     "moe_expert_up_swiglu_gather_packed", "moe_expert_down_packed",
+    "moe_permute_rows_packed", "moe_expert_up_swiglu_packed",
     "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down", "moe_combine", "spec_accept", "moe_hot_experts", "moe_rmsnorm", "specmoe_status_string", "specmoe_abi_version",
     "moe_affinity_table_workspace_bytes", "moe_affinity_table", "moe_nearest_draft_expert",
     "moe_route_topk_draft", "spec_accept_sample", "spec_greedy_tokens", "moe_active_expert_bytes",
@@ -64,6 +65,8 @@ def load_library(build_if_missing: bool = True):
     lib.moe_expert_up_swiglu_gather_packed.argtypes = [vp, ip, i, i, ip, vp, vp, i, i, i, i, i, vp, sz,
                                                        vp, sz, vp]
     lib.moe_expert_down_packed.argtypes = [vp, ip, vp, i, i, i, i, i, vp, vp]
+    lib.moe_permute_rows_packed.argtypes = [vp, ip, i, i, ip, i, i, i, i, vp, sz, vp]
+    lib.moe_expert_up_swiglu_packed.argtypes = [vp, sz, ip, vp, vp, i, i, i, i, i, vp, sz, vp]
     lib.moe_expert_up_swiglu_gather.argtypes = [vp, ip, i, i, ip, vp, vp, i, i, i, i, i, vp, vp]
     lib.moe_expert_down.argtypes = [vp, ip, vp, i, i, i, i, i, vp, vp]
     lib.moe_combine.argtypes = [vp, ip, fp, vp, i, i, i, i, vp, vp]
@@ -83,8 +86,8 @@ def load_library(build_if_missing: bool = True):
     lib.specmoe_abi_version.restype = i
     for name in ("moe_route_topk", "moe_permute", "moe_grouped_swiglu", "moe_combine",
                  "moe_grouped_swiglu_static", "moe_pack_weights",
-                 "moe_expert_up_swiglu_gather_packed", "moe_expert_down_packed", "moe_pack_weights", "moe_packed_h_bytes",
-    "moe_expert_up_swiglu_gather_packed", "moe_expert_down_packed",
+                 "moe_expert_up_swiglu_gather_packed", "moe_expert_down_packed",
+                 "moe_permute_rows_packed", "moe_expert_up_swiglu_packed",
                  "moe_expert_up_swiglu", "moe_expert_up_swiglu_gather", "moe_expert_down",
                  "moe_hot_experts", "moe_affinity_table", "moe_nearest_draft_expert",
                  "moe_route_topk_draft", "spec_accept_sample", "spec_greedy_tokens",
@@ -224,6 +227,28 @@ def moe_expert_up_swiglu_gather_packed(x, row_src, k, expert_offsets, w_gate_pac
         0 if x_packed_workspace is None else
         x_packed_workspace.numel() * x_packed_workspace.element_size(),
         _stream(stream)), "moe_expert_up_swiglu_gather_packed")
+
+
+def moe_permute_rows_packed(x, row_src, k, expert_offsets, n_rows, x_packed, stream=None):
+    T, d = x.shape
+    E = expert_offsets.numel() - 1
+    _check(load_library().moe_permute_rows_packed(
+        _ptr(x, torch.bfloat16, "x"), _ptr(row_src, torch.int32, "row_src"), T, k,
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), n_rows, d, E, BF16,
+        _ptr(x_packed, name="x_packed"), x_packed.numel() * x_packed.element_size(),
+        _stream(stream)), "moe_permute_rows_packed")
+
+
+def moe_expert_up_swiglu_packed(x_packed, expert_offsets, w_gate_packed, w_up_packed, n_rows,
+                                h_packed, stream=None):
+    E, f, d = w_gate_packed.shape
+    _check(load_library().moe_expert_up_swiglu_packed(
+        _ptr(x_packed, name="x_packed"), x_packed.numel() * x_packed.element_size(),
+        _ptr(expert_offsets, torch.int32, "expert_offsets"),
+        _ptr(w_gate_packed, torch.bfloat16, "w_gate_packed"),
+        _ptr(w_up_packed, torch.bfloat16, "w_up_packed"), n_rows, d, f, E, BF16,
+        _ptr(h_packed, name="h_packed"), h_packed.numel() * h_packed.element_size(),
+        _stream(stream)), "moe_expert_up_swiglu_packed")
 
 
 def moe_expert_down_packed(h_packed, expert_offsets, w_down_packed, y_perm, stream=None):

@@ -175,23 +175,61 @@ int moe_expert_up_swiglu_gather_packed(const void* x, const int32_t* row_src, in
     if (h_packed_bytes < moe_packed_h_bytes(n_rows, d_ff, E) || ((uintptr_t)h_packed & 15u) != 0)
         return SPECMOE_ERR_WORKSPACE;
     if (x_packed_workspace) {
-        if (x_packed_workspace_bytes < moe_packed_h_bytes(n_rows, d_model, E) ||
-            ((uintptr_t)x_packed_workspace & 15u) != 0 || ((uintptr_t)x & 15u) != 0)
-            return SPECMOE_ERR_WORKSPACE;
-        const hipError_t e = launch_gather_pack_rows(
-            (const bf16_t*)x, row_src, row_src ? k : 1, expert_offsets, n_rows, E, d_model,
-            (bf16_t*)x_packed_workspace, (hipStream_t)stream);
-        if (e != hipSuccess) return SPECMOE_ERR_DEVICE;
-        return dev(launch_expert_up_bf16_packed_x(
-            (const bf16_t*)x_packed_workspace, expert_offsets, (const bf16_t*)w_gate_packed,
-            (const bf16_t*)w_up_packed, n_rows, d_model, d_ff, E, (bf16_t*)h_packed,
-            (hipStream_t)stream));
+        const int sp = moe_permute_rows_packed(x, row_src, T, k, expert_offsets, n_rows, d_model, E,
+                                               dtype, x_packed_workspace,
+                                               x_packed_workspace_bytes, stream);
+        if (sp != SPECMOE_OK) return sp;
+        return moe_expert_up_swiglu_packed(x_packed_workspace, x_packed_workspace_bytes,
+                                           expert_offsets, w_gate_packed, w_up_packed, n_rows,
+                                           d_model, d_ff, E, dtype, h_packed, h_packed_bytes,
+                                           stream);
     }
     return dev(launch_expert_up_bf16_packed((const bf16_t*)x, expert_offsets,
                                             (const bf16_t*)w_gate_packed,
                                             (const bf16_t*)w_up_packed, n_rows, d_model, d_ff, E,
                                             (bf16_t*)h_packed, (hipStream_t)stream, row_src,
                                             row_src ? k : 1));
+}
+
+int moe_permute_rows_packed(const void* x, const int32_t* row_src, int T, int k,
+                            const int32_t* expert_offsets, int n_rows, int d_model, int E,
+                            int dtype, void* x_packed, size_t x_packed_bytes, void* stream) {
+    if (bad_dtype(dtype)) return SPECMOE_ERR_DTYPE;
+    if (dtype != SPECMOE_BF16) return SPECMOE_ERR_DTYPE;
+    if (n_rows < 0 || d_model < 1 || d_model % 64 != 0 || E < 1 || E > SPECMOE_MAX_EXPERTS)
+        return SPECMOE_ERR_SHAPE;
+    if (row_src) {
+        if (T < 0 || k < 1 || k > SPECMOE_MAX_TOPK || pairs_overflow(T, k) ||
+            (long long)n_rows > (long long)T * k)
+            return SPECMOE_ERR_SHAPE;
+    }
+    if (n_rows == 0) return SPECMOE_OK;
+    if (!x || !expert_offsets || !x_packed) return SPECMOE_ERR_NULL;
+    if (x_packed_bytes < moe_packed_h_bytes(n_rows, d_model, E) ||
+        ((uintptr_t)x_packed & 15u) != 0 || ((uintptr_t)x & 15u) != 0)
+        return SPECMOE_ERR_WORKSPACE;
+    return dev(launch_gather_pack_rows((const bf16_t*)x, row_src, row_src ? k : 1, expert_offsets,
+                                       n_rows, E, d_model, (bf16_t*)x_packed,
+                                       (hipStream_t)stream));
+}
+
+int moe_expert_up_swiglu_packed(const void* x_packed, size_t x_packed_bytes,
+                                const int32_t* expert_offsets, const void* w_gate_packed,
+                                const void* w_up_packed, int n_rows, int d_model, int d_ff, int E,
+                                int dtype, void* h_packed, size_t h_packed_bytes, void* stream) {
+    const int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
+    if (st != SPECMOE_OK) return st;
+    if (dtype != SPECMOE_BF16) return SPECMOE_ERR_DTYPE;
+    if (n_rows == 0) return SPECMOE_OK;
+    if (!x_packed || !expert_offsets || !w_gate_packed || !w_up_packed || !h_packed)
+        return SPECMOE_ERR_NULL;
+    if (h_packed_bytes < moe_packed_h_bytes(n_rows, d_ff, E) || ((uintptr_t)h_packed & 15u) != 0 ||
+        x_packed_bytes < moe_packed_h_bytes(n_rows, d_model, E) || ((uintptr_t)x_packed & 15u) != 0)
+        return SPECMOE_ERR_WORKSPACE;
+    return dev(launch_expert_up_bf16_packed_x(
+        (const bf16_t*)x_packed, expert_offsets, (const bf16_t*)w_gate_packed,
+        (const bf16_t*)w_up_packed, n_rows, d_model, d_ff, E, (bf16_t*)h_packed,
+        (hipStream_t)stream));
 }
 
 int moe_expert_down_packed(const void* h_packed, const int32_t* expert_offsets,
@@ -378,6 +416,6 @@ const char* specmoe_status_string(int status) {
     }
 }
 
-int specmoe_abi_version(void) { return 7; }
+int specmoe_abi_version(void) { return 8; }
 
 }  // extern "C"

@@ -26,50 +26,50 @@ __global__ __launch_bounds__(256) void pack_tiles_kernel(const U128* __restrict_
 // Gather + pack of the activation rows: row block b of the output (numbering: every expert's rows
 // padded to whole 16-row blocks, experts in order) holds rows 16*lb .. 16*lb+15 of its expert,
 // row r of the permuted order being x[row_src[r] / k]; rows beyond the expert's last row are zeros.
-// One workgroup per row block; the block's expert is found with a wave scan over expert_offsets.
+// Workgroup (b, s) writes k-blocks [s * kPackSeg, (s+1) * kPackSeg) of row block b; the block's
+// expert is found with a wave scan over expert_offsets.  A thread keeps one piece position
+// (row r, chunk c) of the 1 KB blocks for the whole segment, so it reads its source row index once.
+constexpr int kPackSeg = 16;                      // k-blocks (1 KB each) per workgroup
+
 __global__ __launch_bounds__(256) void gather_pack_rows_kernel(
     const U128* __restrict__ x, const int32_t* __restrict__ row_src, int topk,
     const int32_t* __restrict__ offsets, int E, int K, U128* __restrict__ dst) {
-    __shared__ int s_row0, s_rows;
-    if (threadIdx.x < kWave) {
-        const int lane = threadIdx.x;
-        int base = 0, row0 = -1, rows = 0;
-        for (int e0 = 0; e0 < E && row0 < 0; e0 += kWave) {
-            const int e = e0 + lane;
-            const int lo = e < E ? offsets[e] : 0, hi = e < E ? offsets[e + 1] : 0;
-            const int nblk = (hi - lo + 15) / 16;
-            int incl = nblk;
+    // every wave works the block's expert out for itself (same answer): no LDS, no barrier
+    const int lane = threadIdx.x % kWave;
+    int base = 0, row0 = -1, rows = 0;
+    for (int e0 = 0; e0 < E && row0 < 0; e0 += kWave) {
+        const int e = e0 + lane;
+        const int lo = e < E ? offsets[e] : 0, hi = e < E ? offsets[e + 1] : 0;
+        const int nblk = (hi - lo + 15) / 16;
+        int incl = nblk;
 #pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                const int v = __shfl_up(incl, off, kWave);
-                if (lane >= off) incl += v;
-            }
-            const unsigned long long hit = __ballot(nblk > 0 && (int)blockIdx.x < base + incl);
-            if (hit) {
-                const int src = __ffsll((long long)hit) - 1;
-                const int lb = (int)blockIdx.x - (base + __shfl(incl, src, kWave) - __shfl(nblk, src, kWave));
-                row0 = __shfl(lo, src, kWave) + lb * 16;
-                rows = min(16, __shfl(hi, src, kWave) - row0);
-            }
-            base += __shfl(incl, kWave - 1, kWave);
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int v = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += v;
         }
-        if (lane == 0) { s_row0 = row0; s_rows = rows; }
+        const unsigned long long hit = __ballot(nblk > 0 && (int)blockIdx.x < base + incl);
+        if (hit) {
+            const int src = __ffsll((long long)hit) - 1;
+            const int lb =
+                (int)blockIdx.x - (base + __shfl(incl, src, kWave) - __shfl(nblk, src, kWave));
+            row0 = __shfl(lo, src, kWave) + lb * 16;
+            rows = min(16, __shfl(hi, src, kWave) - row0);
+        }
+        base += __shfl(incl, kWave - 1, kWave);
     }
-    __syncthreads();
-    const int row0 = s_row0, rows = s_rows;
     if (row0 < 0) return;                         // beyond the last block in use
     const int kblocks = K / pipe::kPackCols;
-    U128* out = dst + (size_t)blockIdx.x * kblocks * 64;
-    for (int g = threadIdx.x; g < kblocks * 64; g += 256) {
-        const int kb = g >> 6, piece = g & 63;
-        const int r = piece >> 2, c = (piece & 3) ^ ((r >> 1) & 3);
-        U128 v = {0, 0, 0, 0};
-        if (r < rows) {
-            const size_t srow = row_src ? (size_t)(row_src[row0 + r] / topk) : (size_t)(row0 + r);
-            v = x[srow * (size_t)(K / 8) + kb * 4 + c];
-        }
-        out[g] = v;
-    }
+    const int kb0 = blockIdx.y * kPackSeg, kb1 = min(kb0 + kPackSeg, kblocks);
+    const int piece = lane, r = piece >> 2, c = (piece & 3) ^ ((r >> 1) & 3);
+    const bool live = r < rows;
+    size_t srow = 0;
+    if (live) srow = row_src ? (size_t)(row_src[row0 + r] / topk) : (size_t)(row0 + r);
+    const U128* in = x + srow * (size_t)(K / 8) + c;
+    U128* out = dst + (size_t)blockIdx.x * kblocks * 64 + piece;
+    const U128 zero = {0, 0, 0, 0};
+#pragma unroll 4
+    for (int kb = kb0 + (int)(threadIdx.x / kWave); kb < kb1; kb += 4)
+        out[(size_t)kb * 64] = live ? in[kb * 4] : zero;
 }
 
 }  // namespace
@@ -78,7 +78,9 @@ hipError_t launch_gather_pack_rows(const bf16_t* x, const int32_t* row_src, int 
                                    const int32_t* offsets, int n_rows, int E, int K,
                                    bf16_t* dst, hipStream_t s) {
     const int max_blocks = n_rows / 16 + E;       // sum_e ceil(M_e / 16) <= n_rows / 16 + E
-    hipLaunchKernelGGL(gather_pack_rows_kernel, dim3((unsigned)max_blocks), dim3(256), 0, s,
+    const int segs = (K / pipe::kPackCols + kPackSeg - 1) / kPackSeg;
+    hipLaunchKernelGGL(gather_pack_rows_kernel, dim3((unsigned)max_blocks, (unsigned)segs),
+                       dim3(256), 0, s,
                        reinterpret_cast<const U128*>(x), row_src, topk, offsets, E, K,
                        reinterpret_cast<U128*>(dst));
     return hipGetLastError();

@@ -54,8 +54,9 @@ class MoEVerifyLayer:
     def forward(self, x, w_router, w_gate, w_up, w_down, bias=None, residual=None, out=None,
                 stream=None, marks=None, draft_remap=None, packed=None):
         """Enqueues the layer.  `marks`, if given, is a sequence of six torch events recorded on
-        `stream` before the router and after each of the five calls (route, permute, gate/up,
-        down, combine): the benchmark's per-kernel times.
+        `stream` before the router and after each of the five steps (route, permute, gate/up,
+        down, combine): the benchmark's per-kernel times.  On the tile-packed path the permute
+        step includes the gather of the token rows into tile-packed form.
         `draft_remap` ([E] int32 from moe_nearest_draft_expert) switches to the draft model's
         routing: selected experts that are not resident are replaced by their nearest draft
         expert, so only draft experts compute.
@@ -76,8 +77,6 @@ class MoEVerifyLayer:
             marks[1].record(stream)
         B.moe_permute(x, self.topk_idx, self.E, None if self.fuse_gather else self.x_perm,
                       self.expert_offsets, self.row_src, self.row_of, stream)
-        if marks is not None:
-            marks[2].record(stream)
         if use_packed:
             if self.h_packed is None:
                 self.h_packed = torch.empty(
@@ -86,10 +85,19 @@ class MoEVerifyLayer:
                 self.x_packed = torch.empty(
                     (B.moe_packed_h_bytes(self.T * self.k, self.d, self.E),), dtype=torch.uint8,
                     device=self.h.device)
+            if self.pack_x:
+                # the data movement of the permute step, written once in the GEMM's own layout
+                B.moe_permute_rows_packed(x, self.row_src, self.k, self.expert_offsets,
+                                          self.T * self.k, self.x_packed, stream)
+        if marks is not None:
+            marks[2].record(stream)
+        if use_packed and self.pack_x:
+            B.moe_expert_up_swiglu_packed(self.x_packed, self.expert_offsets, packed["w_gate"],
+                                          packed["w_up"], self.T * self.k, self.h_packed, stream)
+        elif use_packed:
             B.moe_expert_up_swiglu_gather_packed(x, self.row_src, self.k, self.expert_offsets,
                                                  packed["w_gate"], packed["w_up"],
-                                                 self.T * self.k, self.h_packed,
-                                                 self.x_packed if self.pack_x else None, stream)
+                                                 self.T * self.k, self.h_packed, None, stream)
         elif self.fuse_gather:
             B.moe_expert_up_swiglu_gather(x, self.row_src, self.k, self.expert_offsets, w_gate,
                                           w_up, self.h, stream)

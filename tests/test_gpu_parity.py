@@ -654,10 +654,26 @@ def test_packed_expert_gemms(d, f, rows):
     y3 = torch.full_like(y, float("nan"))
     sm.moe_expert_up_swiglu_gather_packed(dev(xp), None, 1, doff, pk["w_gate"], pk["w_up"], n, hp2, xws)
     sm.moe_expert_down_packed(hp2, doff, pk["w_down"], y3)
+    # ... and as the two calls of their own (permute step writes the packed rows, then the GEMM)
+    hp3 = torch.full_like(hp, 0xcc)
+    xws3 = torch.full_like(xws, 0xbb)
+    sm.moe_permute_rows_packed(dev(xp), None, 1, doff, n, xws3)
+    sm.moe_expert_up_swiglu_packed(xws3, doff, pk["w_gate"], pk["w_up"], n, hp3)
     torch.cuda.synchronize()
     assert torch.equal(y.view(torch.int16), y3.view(torch.int16))
     used = (sum((r + 15) // 16 for r in rows)) * 16 * f * 2          # blocks the batch really uses
     assert torch.equal(hp[:used], hp2[:used])
+    assert torch.equal(hp[:used], hp3[:used])
+    usedx = used // f * d
+    assert torch.equal(xws[:usedx], xws3[:usedx])
+    # the packed rows are the tile-packed image of x_perm, padding rows zero
+    xpad = torch.zeros(usedx // (2 * d), d, dtype=torch.bfloat16)
+    b = 0
+    for e, r in enumerate(rows):
+        xpad[16 * b:16 * b + r] = xp[off[e]:off[e + 1]]
+        b += (r + 15) // 16
+    assert (xws3[:usedx].cpu().view(torch.int16).numpy() ==
+            _tile_packed(xpad[None]).reshape(-1)).all()
     ey = orc.grouped_swiglu(f64(xp), off, LazyF64(wg), LazyF64(wu), LazyF64(wd))
     check_float(f64(y), ey, torch.bfloat16, f"packed rows={rows}")
     if n >= 192 * E:

@@ -29,7 +29,7 @@ def test_header_and_library_agree(lib):
     assert set(declared) == set(binding.EXPORTED_SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.specmoe_abi_version() == 7
+    assert lib.specmoe_abi_version() == 8
 
 
 def test_status_strings(lib):
@@ -77,6 +77,19 @@ def test_packed_entry_points_validation(lib):
     assert up(P, N, 0, 1, P, P, P, 64, 64, 64, 2, 1, P, 1 << 30, P, 16, N) == 4  # x workspace too small
     assert down(P, P, P, 64, 64, 64, 2, 0, P, N) == 3
     assert down(N, P, P, 64, 64, 64, 2, 1, P, N) == 1
+    rows, upp = lib.moe_permute_rows_packed, lib.moe_expert_up_swiglu_packed
+    big = 1 << 30
+    assert rows(P, N, 0, 1, P, 64, 64, 2, 0, P, big, N) == 3             # bf16 only
+    assert rows(P, N, 0, 1, P, 64, 60, 2, 1, P, big, N) == 2             # d_model % 64
+    assert rows(P, P, 8, 2, P, 64, 64, 2, 1, P, big, N) == 2             # n_rows > T*k
+    assert rows(P, N, 0, 1, P, 64, 64, 2, 1, P, 16, N) == 4              # x_packed too small
+    assert rows(P, N, 0, 1, N, 64, 64, 2, 1, P, big, N) == 1
+    assert rows(N, N, 0, 1, N, 0, 64, 2, 1, N, 0, N) == 0                # nothing to do
+    assert upp(P, big, P, P, P, 64, 64, 64, 2, 0, P, big, N) == 3
+    assert upp(P, 16, P, P, P, 64, 64, 64, 2, 1, P, big, N) == 4         # x_packed too small
+    assert upp(P, big, P, P, P, 64, 64, 64, 2, 1, P, 16, N) == 4         # h_packed too small
+    assert upp(N, big, P, P, P, 64, 64, 64, 2, 1, P, big, N) == 1
+    assert upp(P, big, P, P, P, 64, 64, 100, 2, 1, P, big, N) == 2
 
 
 def test_route_validation(lib):
