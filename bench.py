@@ -203,7 +203,7 @@ class LayerRun:
         self.toks = torch.empty(self.B, self.gamma + 1, dtype=torch.int32, device="cuda")
         self.stream = torch.cuda.current_stream()
         self.draft_remap = draft_remap
-        self.packed = packed      # tile-packed expert weights (used by the layer for large batches)
+        self.packed = packed      # tile-packed expert weights (the layer decides where to use them)
 
     def step(self, marks=None):
         L = self.L
@@ -253,8 +253,9 @@ class LayerRun:
             whole.append(m[0].elapsed_time(m[6]))
         counts = (self.layer.expert_offsets[1:] - self.layer.expert_offsets[:-1]).cpu()
         active = int((counts > 0).sum())
-        packed_rows = (self.packed is not None and self.layer.pack_x and
-                       self.T * self.cfg.k >= self.layer.PACKED_MIN_ROWS_PER_EXPERT * self.cfg.E)
+        packed_rows = (self.packed is not None and self.cfg.dtype == "bf16" and
+                       self.layer.packed_plan(self.T * self.cfg.k, self.cfg.E, self.cfg.d_model,
+                                              self.cfg.d_ff)[0])
         work = algorithmic_work(self.cfg, self.T, active, rows_materialised=packed_rows)
         kernels = {}
         for n in KERNELS:
@@ -271,21 +272,36 @@ class LayerRun:
             kernels[n] = e
         return {"ms_per_step": wall_ms, "ms_per_step_median": statistics.median(group_ms),
                 "ms_per_step_instrumented_median": statistics.median(whole),
-                "kernels": kernels, "active_experts": active,
+                "kernels": kernels, "active_experts": active, "packed_up": bool(packed_rows),
                 "max_rows_per_expert": int(counts.max()), "min_rows_per_expert": int(counts.min())}
 
 
-def kernel_name(cfg, T):
-    """Which gate/up kernel the library's dispatch picks for this shape (names for the report)."""
+def packed_weights_for(sm, torch, cfg, L, T, row_major=False):
+    """Tile-packed copies of the expert weights if the layer runs any projection of a T-token
+    batch on them (one-time re-layout, outside every timed region: the weights are resident model
+    parameters); None otherwise."""
+    if cfg.dtype != "bf16" or row_major:
+        return None
+    if not sm.MoEVerifyLayer.packed_plan(T * cfg.k, cfg.E, cfg.d_model, cfg.d_ff)[0]:
+        return None
+    packed = sm.MoEVerifyLayer.pack_weights(L["w_gate"], L["w_up"], L["w_down"])
+    torch.cuda.synchronize()
+    return packed
+
+
+def kernel_name(cfg, T, packed=True):
+    """Which gate/up kernel runs for this shape (names for the report)."""
+    import paper_2604_10152_amd as sm
     if cfg.dtype != "bf16":
         return "grouped_gemm_f32_kernel<true> (gate/up + SwiGLU)"
     rows = T * cfg.k
-    if rows >= 192 * cfg.E:
-        return ("grouped_gemm_bf16_pipe16_kernel<PipeCfg<320,256,32,4,2,4,true>> (gate/up + SwiGLU; "
-                "tile-packed operands unless --row-major: the permute step then writes the "
-                "dispatched rows tile-packed)")
-    if cfg.d_model >= 4096 and rows >= 48 * cfg.E:
-        return "grouped_gemm_bf16_pipe16_kernel<PipeCfg<192,256,32,4,2,4,true>> (gate/up + SwiGLU)"
+    tile = 320 if rows >= 192 * cfg.E else 192
+    if packed and sm.MoEVerifyLayer.packed_plan(rows, cfg.E, cfg.d_model, cfg.d_ff)[0]:
+        return (f"grouped_gemm_bf16_pipe16_kernel<PipeCfg<{tile},256,32,4,2,4,true>,PA,PB> (gate/up + "
+                "SwiGLU on tile-packed operands: the permute step writes the dispatched rows "
+                "tile-packed)")
+    if rows >= 192 * cfg.E or (cfg.d_model >= 4096 and rows >= 48 * cfg.E):
+        return f"grouped_gemm_bf16_pipe16_kernel<PipeCfg<{tile},256,32,4,2,4,true>> (gate/up + SwiGLU)"
     if cfg.d_model >= 4096:
         return "grouped_gemm_bf16_pipe_kernel<PipeCfg<64,128,64,4,1,2,true>> (gate/up + SwiGLU)"
     return "grouped_gemm_bf16_kernel<TileCfg<64,256,1,4,true>> (gate/up + SwiGLU)"
@@ -300,7 +316,7 @@ def roofline_of(cfg, T, m, mfma_bound):
     else:
         r = {"bound": "hbm", "achieved": up["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     r["frac"] = r["achieved"] / r["peak"]
-    r["kernel"] = kernel_name(cfg, T)
+    r["kernel"] = kernel_name(cfg, T, packed=m.get("packed_up", False))
     r["kernel_ms"] = up["us"] * 1e-3
     r["traffic"] = None
     return r
@@ -332,7 +348,8 @@ def summary(cfg, T, m):
             "roofline": roofline_of(cfg, T, m, mfma_bound=False)}
 
 
-def paper_quantities(torch, sm, synth, cfg, L, B, gamma, steps, warmup, seed, t_verify_ms=None):
+def paper_quantities(torch, sm, synth, cfg, L, B, gamma, steps, warmup, seed, t_verify_ms=None,
+                     packed=None):
     """lambda, c and the Eq. 2 estimate for this layer at batch size B and draft length gamma
     (Sec. 3.3): lambda = T<B*(gamma+1)> / T<B> on the same weights, c = T_draft<B> / T_target<B>
     with the draft model = the same layer restricted to the E/4 most activated experts of the
@@ -341,14 +358,16 @@ def paper_quantities(torch, sm, synth, cfg, L, B, gamma, steps, warmup, seed, t_
     import dataclasses
     E, k = cfg.E, cfg.k
     if t_verify_ms is None:
-        ver = LayerRun(torch, sm, synth, cfg, L, T=B * (gamma + 1), B=B, gamma=gamma, seed=seed)
+        ver = LayerRun(torch, sm, synth, cfg, L, T=B * (gamma + 1), B=B, gamma=gamma, seed=seed,
+                       packed=packed)
         t_verify_ms = ver.measure(steps, warmup)["ms_per_step_median"]
         offsets = ver.layer.expert_offsets
     else:
-        ver = LayerRun(torch, sm, synth, cfg, L, T=B * (gamma + 1), B=B, gamma=gamma, seed=seed)
+        ver = LayerRun(torch, sm, synth, cfg, L, T=B * (gamma + 1), B=B, gamma=gamma, seed=seed,
+                       packed=packed)
         ver.step()
         offsets = ver.layer.expert_offsets
-    tgt = LayerRun(torch, sm, synth, cfg, L, T=B, B=B, gamma=gamma, seed=seed)
+    tgt = LayerRun(torch, sm, synth, cfg, L, T=B, B=B, gamma=gamma, seed=seed, packed=packed)
     t_target_ms = tgt.measure(steps, warmup)["ms_per_step_median"]
     n_draft = max(k, E // 4)
     table = torch.empty((E, E), dtype=torch.float32, device="cuda")
@@ -358,7 +377,8 @@ def paper_quantities(torch, sm, synth, cfg, L, B, gamma, steps, warmup, seed, t_
     remap = torch.empty((E,), dtype=torch.int32, device="cuda")
     sm.moe_hot_experts(offsets, hot)
     sm.moe_nearest_draft_expert(table, hot, remap)
-    drf = LayerRun(torch, sm, synth, cfg, L, T=B, B=B, gamma=gamma, seed=seed, draft_remap=remap)
+    drf = LayerRun(torch, sm, synth, cfg, L, T=B, B=B, gamma=gamma, seed=seed, draft_remap=remap,
+                   packed=packed)
     t_draft_ms = drf.measure(steps, warmup)["ms_per_step_median"]
     # tau: synthetic acceptance with match probability 0.7 through spec_accept
     ids_cfg = dataclasses.replace(cfg, match_prob=0.7)
@@ -462,9 +482,7 @@ def traffic_run(args):
     torch.cuda.synchronize()
     cfg = synth.CONFIGS[args.config]
     L = synth.make_layer(cfg, "cuda", seed=args.seed)
-    packed = None
-    if cfg.dtype == "bf16" and cfg.P >= 192 * cfg.E and not args.row_major:
-        packed = sm.MoEVerifyLayer.pack_weights(L["w_gate"], L["w_up"], L["w_down"])
+    packed = packed_weights_for(sm, torch, cfg, L, cfg.T, args.row_major)
     run = LayerRun(torch, sm, synth, cfg, L, seed=args.seed, packed=packed)
     for _ in range(3):
         run.step()
@@ -580,12 +598,7 @@ def main():
         print(json.dumps(out))
         return
     L = synth.make_layer(cfg, "cuda", seed=args.seed)
-    packed = None
-    if cfg.dtype == "bf16" and cfg.P >= 192 * cfg.E and not args.row_major:
-        # one-time re-layout of the expert weights for the large-batch kernels, outside the timed
-        # region like every other input preparation (the weights are resident model parameters)
-        packed = sm.MoEVerifyLayer.pack_weights(L["w_gate"], L["w_up"], L["w_down"])
-        torch.cuda.synchronize()
+    packed = packed_weights_for(sm, torch, cfg, L, cfg.T, args.row_major)
     run = LayerRun(torch, sm, synth, cfg, L, seed=args.seed, packed=packed)
     if args.graph:
         graphed = sm.GraphedStep(lambda st: (
@@ -622,8 +635,9 @@ def main():
                    "active_experts": m["active_experts"],
                    "max_rows_per_expert": m["max_rows_per_expert"],
                    "min_rows_per_expert": m["min_rows_per_expert"],
-                   "expert_weight_layout": "tile-packed (moe_pack_weights, once, outside the timed "
-                                           "region)" if packed is not None else "row-major"},
+                   "expert_weight_layout": "tile-packed copies next to the row-major weights "
+                                           "(moe_pack_weights, once, outside the timed region)"
+                                           if packed is not None else "row-major"},
         "launch": "hip-graph" if args.graph else "eager",
         "tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else None,
         "hbm_frac": hbm_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
@@ -637,21 +651,23 @@ def main():
         # same weights, the 80-token batch of the Mixtral-shaped configuration (B=16, gamma=4):
         # the memory-bound end of the same layer
         c2 = synth.CONFIGS[2]
-        r2 = LayerRun(torch, sm, synth, c2, L, seed=args.seed)
+        r2 = LayerRun(torch, sm, synth, c2, L, seed=args.seed, packed=packed)
         also[c2.name] = summary(c2, c2.T, r2.measure(steps2, args.warmup))
         out["paper_quantities"] = [
             paper_quantities(torch, sm, synth, c2, L, c2.B, c2.gamma, steps2, 5, args.seed,
-                             t_verify_ms=also[c2.name]["ms_per_step_median"]),
+                             t_verify_ms=also[c2.name]["ms_per_step_median"], packed=packed),
             paper_quantities(torch, sm, synth, cfg, L, cfg.B, cfg.gamma, steps2, 5, args.seed,
-                             t_verify_ms=m["ms_per_step_median"]),
+                             t_verify_ms=m["ms_per_step_median"], packed=packed),
         ]
         del r2
         for cid in (3, 6):
             cc = synth.CONFIGS[cid]
             Lc = synth.make_layer(cc, "cuda", seed=cid)
-            rc = LayerRun(torch, sm, synth, cc, Lc, seed=cid)
+            pc = packed_weights_for(sm, torch, cc, Lc, cc.T, args.row_major)
+            rc = LayerRun(torch, sm, synth, cc, Lc, seed=cid, packed=pc)
             also[cc.name] = summary(cc, cc.T, rc.measure(steps2, args.warmup))
-            del Lc, rc
+            also[cc.name]["expert_weight_layout"] = "tile-packed" if pc is not None else "row-major"
+            del Lc, rc, pc
             torch.cuda.empty_cache()
         out["also"] = also
     if not args.no_cpu_baseline:

@@ -149,12 +149,19 @@ int moe_expert_up_swiglu_gather(const void* x, const int32_t* row_src, int T, in
  *     workspace, as calls of their own (the packed rows are then the caller's buffer: the token
  *     dispatch of Sec. 2.1 written once in the layout the GEMM loads).  moe_permute_rows_packed
  *     gathers x[row_src[r] / k] (row_src == NULL: x[r]) into x_packed, row numbering as for h,
- *     padding rows zero; x 16-byte aligned.  moe_expert_up_swiglu_packed reads such an x_packed.
- *     x_packed_bytes >= moe_packed_h_bytes(n_rows, d_model, E).
+ *     padding rows zero; x 16-byte aligned.  moe_expert_up_swiglu_packed reads such an x_packed
+ *     (x_packed_bytes >= moe_packed_h_bytes(n_rows, d_model, E)) and writes h tile-packed
+ *     (h_row_major == 0, h_bytes >= moe_packed_h_bytes(n_rows, d_ff, E)) or as the row-major
+ *     [n_rows, d_ff] matrix moe_expert_down reads (h_row_major != 0, h_bytes >= n_rows*d_ff*2):
+ *     with tens of rows per expert the packed gate/up kernel is ahead of the row-major one while
+ *     the row-major down kernels are ahead of the packed one.
  *   moe_expert_down_packed: as moe_expert_down with h and w_down tile-packed; y_perm row-major.
  * Results are identical to the row-major entry points' large-batch kernels (same arithmetic in
- * the same order).  These calls run the large-batch kernel whatever n_rows is; callers with few
- * rows per expert should use the row-major entry points.  bf16 only. */
+ * the same order) where both pick the same tile.  moe_expert_up_swiglu_packed and
+ * moe_expert_down_packed choose 320-row tiles from 192 rows per expert on average and 192-row
+ * tiles below; moe_expert_up_swiglu_gather_packed without a workspace always uses 320-row tiles.
+ * With long contractions (>= 4096) and fewer than about 48 rows per expert the row-major entry
+ * points are the faster ones.  bf16 only. */
 int moe_pack_weights(const void* w, int E, int n_rows, int n_cols, int dtype, void* w_packed,
                      void* stream);
 size_t moe_packed_h_bytes(int n_rows, int d_ff, int E);
@@ -170,7 +177,7 @@ int moe_permute_rows_packed(const void* x, const int32_t* row_src, int T, int k,
 int moe_expert_up_swiglu_packed(const void* x_packed, size_t x_packed_bytes,
                                 const int32_t* expert_offsets, const void* w_gate_packed,
                                 const void* w_up_packed, int n_rows, int d_model, int d_ff, int E,
-                                int dtype, void* h_packed, size_t h_packed_bytes, void* stream);
+                                int dtype, void* h, size_t h_bytes, int h_row_major, void* stream);
 int moe_expert_down_packed(const void* h_packed, const int32_t* expert_offsets,
                            const void* w_down_packed, int n_rows, int d_model, int d_ff, int E,
                            int dtype, void* y_perm, void* stream);

@@ -66,7 +66,7 @@ def load_library(build_if_missing: bool = True):
                                                        vp, sz, vp]
     lib.moe_expert_down_packed.argtypes = [vp, ip, vp, i, i, i, i, i, vp, vp]
     lib.moe_permute_rows_packed.argtypes = [vp, ip, i, i, ip, i, i, i, i, vp, sz, vp]
-    lib.moe_expert_up_swiglu_packed.argtypes = [vp, sz, ip, vp, vp, i, i, i, i, i, vp, sz, vp]
+    lib.moe_expert_up_swiglu_packed.argtypes = [vp, sz, ip, vp, vp, i, i, i, i, i, vp, sz, i, vp]
     lib.moe_expert_up_swiglu_gather.argtypes = [vp, ip, i, i, ip, vp, vp, i, i, i, i, i, vp, vp]
     lib.moe_expert_down.argtypes = [vp, ip, vp, i, i, i, i, i, vp, vp]
     lib.moe_combine.argtypes = [vp, ip, fp, vp, i, i, i, i, vp, vp]
@@ -239,15 +239,15 @@ def moe_permute_rows_packed(x, row_src, k, expert_offsets, n_rows, x_packed, str
         _stream(stream)), "moe_permute_rows_packed")
 
 
-def moe_expert_up_swiglu_packed(x_packed, expert_offsets, w_gate_packed, w_up_packed, n_rows,
-                                h_packed, stream=None):
+def moe_expert_up_swiglu_packed(x_packed, expert_offsets, w_gate_packed, w_up_packed, n_rows, h,
+                                h_row_major=False, stream=None):
     E, f, d = w_gate_packed.shape
     _check(load_library().moe_expert_up_swiglu_packed(
         _ptr(x_packed, name="x_packed"), x_packed.numel() * x_packed.element_size(),
         _ptr(expert_offsets, torch.int32, "expert_offsets"),
         _ptr(w_gate_packed, torch.bfloat16, "w_gate_packed"),
         _ptr(w_up_packed, torch.bfloat16, "w_up_packed"), n_rows, d, f, E, BF16,
-        _ptr(h_packed, name="h_packed"), h_packed.numel() * h_packed.element_size(),
+        _ptr(h, name="h"), h.numel() * h.element_size(), 1 if h_row_major else 0,
         _stream(stream)), "moe_expert_up_swiglu_packed")
 
 

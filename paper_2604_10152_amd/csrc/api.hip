@@ -181,7 +181,7 @@ int moe_expert_up_swiglu_gather_packed(const void* x, const int32_t* row_src, in
         if (sp != SPECMOE_OK) return sp;
         return moe_expert_up_swiglu_packed(x_packed_workspace, x_packed_workspace_bytes,
                                            expert_offsets, w_gate_packed, w_up_packed, n_rows,
-                                           d_model, d_ff, E, dtype, h_packed, h_packed_bytes,
+                                           d_model, d_ff, E, dtype, h_packed, h_packed_bytes, 0,
                                            stream);
     }
     return dev(launch_expert_up_bf16_packed((const bf16_t*)x, expert_offsets,
@@ -216,19 +216,22 @@ int moe_permute_rows_packed(const void* x, const int32_t* row_src, int T, int k,
 int moe_expert_up_swiglu_packed(const void* x_packed, size_t x_packed_bytes,
                                 const int32_t* expert_offsets, const void* w_gate_packed,
                                 const void* w_up_packed, int n_rows, int d_model, int d_ff, int E,
-                                int dtype, void* h_packed, size_t h_packed_bytes, void* stream) {
+                                int dtype, void* h, size_t h_bytes, int h_row_major,
+                                void* stream) {
     const int st = check_expert_shapes(n_rows, d_model, d_ff, E, dtype);
     if (st != SPECMOE_OK) return st;
     if (dtype != SPECMOE_BF16) return SPECMOE_ERR_DTYPE;
     if (n_rows == 0) return SPECMOE_OK;
-    if (!x_packed || !expert_offsets || !w_gate_packed || !w_up_packed || !h_packed)
+    if (!x_packed || !expert_offsets || !w_gate_packed || !w_up_packed || !h)
         return SPECMOE_ERR_NULL;
-    if (h_packed_bytes < moe_packed_h_bytes(n_rows, d_ff, E) || ((uintptr_t)h_packed & 15u) != 0 ||
+    const size_t h_need = h_row_major ? (size_t)n_rows * (size_t)d_ff * 2
+                                      : moe_packed_h_bytes(n_rows, d_ff, E);
+    if (h_bytes < h_need || ((uintptr_t)h & 15u) != 0 ||
         x_packed_bytes < moe_packed_h_bytes(n_rows, d_model, E) || ((uintptr_t)x_packed & 15u) != 0)
         return SPECMOE_ERR_WORKSPACE;
     return dev(launch_expert_up_bf16_packed_x(
         (const bf16_t*)x_packed, expert_offsets, (const bf16_t*)w_gate_packed,
-        (const bf16_t*)w_up_packed, n_rows, d_model, d_ff, E, (bf16_t*)h_packed,
+        (const bf16_t*)w_up_packed, n_rows, d_model, d_ff, E, (bf16_t*)h, h_row_major != 0,
         (hipStream_t)stream));
 }
 

@@ -87,8 +87,8 @@ hipError_t launch_expert_down_bf16_packed(const bf16_t* h_packed, const int32_t*
                                           int E, bf16_t* y, hipStream_t s);
 hipError_t launch_expert_up_bf16_packed_x(const bf16_t* x_packed, const int32_t* offsets,
                                           const bf16_t* wg_packed, const bf16_t* wu_packed,
-                                          int n_rows, int d, int f, int E, bf16_t* h_packed,
-                                          hipStream_t s);
+                                          int n_rows, int d, int f, int E, bf16_t* h,
+                                          bool h_row_major, hipStream_t s);
 hipError_t launch_gather_pack_rows(const bf16_t* x, const int32_t* row_src, int topk,
                                    const int32_t* offsets, int n_rows, int E, int K,
                                    bf16_t* dst, hipStream_t s);

@@ -345,18 +345,34 @@ hipError_t launch_expert_up_bf16_packed(const bf16_t* x, const int32_t* offsets,
         x, offsets, wg_packed, wu_packed, n_rows, E, f, d, h_packed, s, row_src, topk);
 }
 
+// Tile height by the average rows per expert, as for the row-major operands: 320-row tiles from
+// 192 rows per expert, 192-row tiles below.  h_row_major: h is written [n_rows, f] row-major
+// (for a down projection on row-major operands) instead of tile-packed.
 hipError_t launch_expert_up_bf16_packed_x(const bf16_t* x_packed, const int32_t* offsets,
                                           const bf16_t* wg_packed, const bf16_t* wu_packed,
-                                          int n_rows, int d, int f, int E, bf16_t* h_packed,
-                                          hipStream_t s) {
-    return launch_pipe16<PipeCfg<320, 256, 32, 4, 2, 4, true>, true, true, true>(
-        x_packed, offsets, wg_packed, wu_packed, n_rows, E, f, d, h_packed, s);
+                                          int n_rows, int d, int f, int E, bf16_t* h,
+                                          bool h_row_major, hipStream_t s) {
+    typedef PipeCfg<320, 256, 32, 4, 2, 4, true> Large;
+    typedef PipeCfg<192, 256, 32, 4, 2, 4, true> Mid;
+    const bool large = (long long)n_rows >= 192ll * E;
+    if (h_row_major)
+        return large ? launch_pipe16<Large, true, true, false>(x_packed, offsets, wg_packed,
+                                                               wu_packed, n_rows, E, f, d, h, s)
+                     : launch_pipe16<Mid, true, true, false>(x_packed, offsets, wg_packed,
+                                                             wu_packed, n_rows, E, f, d, h, s);
+    return large ? launch_pipe16<Large, true, true, true>(x_packed, offsets, wg_packed, wu_packed,
+                                                          n_rows, E, f, d, h, s)
+                 : launch_pipe16<Mid, true, true, true>(x_packed, offsets, wg_packed, wu_packed,
+                                                        n_rows, E, f, d, h, s);
 }
 
 hipError_t launch_expert_down_bf16_packed(const bf16_t* h_packed, const int32_t* offsets,
                                           const bf16_t* wd_packed, int n_rows, int d, int f,
                                           int E, bf16_t* y, hipStream_t s) {
-    return launch_pipe16<PipeCfg<320, 256, 32, 4, 2, 4, false>, true, true, false>(
+    if ((long long)n_rows >= 192ll * E)
+        return launch_pipe16<PipeCfg<320, 256, 32, 4, 2, 4, false>, true, true, false>(
+            h_packed, offsets, wd_packed, nullptr, n_rows, E, d, f, y, s);
+    return launch_pipe16<PipeCfg<192, 256, 32, 4, 2, 4, false>, true, true, false>(
         h_packed, offsets, wd_packed, nullptr, n_rows, E, d, f, y, s);
 }
 

@@ -268,7 +268,10 @@ template <typename T, int V>
 void launch_typed(const void* x, const void* wr, const float* bias, int Tn, int d, int E, int k,
                   int renorm, int32_t* idx, float* w, const int32_t* remap, hipStream_t s) {
     const bool vec = (d % V == 0) && ((((uintptr_t)x | (uintptr_t)wr) & 15u) == 0);
-    const bool many = Tn > 256;                       // more tokens than CUs: 4 tokens per workgroup
+    // One token per workgroup while two workgroups per CU cover the batch (a single pass over
+    // the experts, nothing converted twice); beyond that 4 tokens share every widened router
+    // weight.
+    const bool many = Tn > 512;
     const T* xt = (const T*)x;
     const T* wt = (const T*)wr;
     if (vec && many) launch_by_experts<T, true, 4>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);

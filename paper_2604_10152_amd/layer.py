@@ -14,12 +14,11 @@ class MoEVerifyLayer:
     """
 
     def __init__(self, T, d_model, d_ff, E, k, dtype, device="cuda", renorm=True,
-                 fuse_gather=True, pack_x=True):
+                 fuse_gather=True):
         """fuse_gather: moe_permute writes indices only and the gate/up GEMM gathers token rows
         itself (moe_expert_up_swiglu_gather); False materialises x_perm first."""
         self.T, self.d, self.f, self.E, self.k = T, d_model, d_ff, E, k
         self.dtype, self.renorm = dtype, renorm
-        self.pack_x = pack_x       # packed path: gather the token rows into tile-packed form first
         self.fuse_gather = fuse_gather and T * d_model * (4 if dtype == torch.float32 else 2) < 2 ** 32
         P = T * k
         dev = torch.device(device)
@@ -36,14 +35,26 @@ class MoEVerifyLayer:
         self.h_packed = None                     # allocated on first use of packed weights
         self.x_packed = None
 
-    # rows per expert (average) from which the tile-packed large-batch path pays off
-    PACKED_MIN_ROWS_PER_EXPERT = 192
+    # Which projections run on tile-packed operands (measured crossovers, average rows per
+    # expert r = T*k/E): the packed gate/up kernel is ahead from r >= 48, and at any r when the
+    # contraction is short (d_model < 4096, where the row-major alternative is the
+    # register-staged kernel); the packed down kernel from r >= 96, or with d_ff < 4096.
+    PACKED_UP_MIN_ROWS = 48
+    PACKED_DOWN_MIN_ROWS = 96
+
+    @classmethod
+    def packed_plan(cls, n_pairs, E, d_model, d_ff):
+        """(gate/up on packed operands?, down on packed operands?) for a batch of n_pairs
+        (token, expert) pairs."""
+        up = n_pairs >= cls.PACKED_UP_MIN_ROWS * E or d_model < 4096
+        down = up and (n_pairs >= cls.PACKED_DOWN_MIN_ROWS * E or d_ff < 4096)
+        return up, down
 
     @staticmethod
     def pack_weights(w_gate, w_up, w_down, stream=None):
-        """One-time re-layout of the expert weights for the large-batch path (bf16 only):
+        """One-time re-layout of the expert weights for the tile-packed kernels (bf16 only):
         returns the dict to pass as `packed=` to forward().  The row-major tensors stay valid and
-        are still used whenever a batch is too small for that path."""
+        are still used whenever packed_plan() sends a projection to the row-major kernels."""
         out = {}
         for name, w in (("w_gate", w_gate), ("w_up", w_up), ("w_down", w_down)):
             wp = torch.empty_like(w)
@@ -60,11 +71,12 @@ class MoEVerifyLayer:
         `draft_remap` ([E] int32 from moe_nearest_draft_expert) switches to the draft model's
         routing: selected experts that are not resident are replaced by their nearest draft
         expert, so only draft experts compute.
-        `packed` (from pack_weights) switches the two expert GEMMs to the tile-packed entry points
-        when the batch is large enough (bf16, at least 192 rows per expert on average)."""
+        `packed` (from pack_weights) lets the expert GEMMs run on tile-packed operands where
+        packed_plan() says they are the faster ones (bf16 only)."""
         out = self.out if out is None else out
-        use_packed = (packed is not None and self.dtype == torch.bfloat16 and self.fuse_gather and
-                      self.T * self.k >= self.PACKED_MIN_ROWS_PER_EXPERT * self.E)
+        up_packed = down_packed = False
+        if packed is not None and self.dtype == torch.bfloat16 and self.fuse_gather:
+            up_packed, down_packed = self.packed_plan(self.T * self.k, self.E, self.d, self.f)
         if marks is not None:
             marks[0].record(stream)
         if draft_remap is None:
@@ -77,27 +89,25 @@ class MoEVerifyLayer:
             marks[1].record(stream)
         B.moe_permute(x, self.topk_idx, self.E, None if self.fuse_gather else self.x_perm,
                       self.expert_offsets, self.row_src, self.row_of, stream)
-        if use_packed:
-            if self.h_packed is None:
-                self.h_packed = torch.empty(
-                    (B.moe_packed_h_bytes(self.T * self.k, self.f, self.E),), dtype=torch.uint8,
-                    device=self.h.device)
+        if up_packed:
+            if self.x_packed is None:
                 self.x_packed = torch.empty(
                     (B.moe_packed_h_bytes(self.T * self.k, self.d, self.E),), dtype=torch.uint8,
                     device=self.h.device)
-            if self.pack_x:
-                # the data movement of the permute step, written once in the GEMM's own layout
-                B.moe_permute_rows_packed(x, self.row_src, self.k, self.expert_offsets,
-                                          self.T * self.k, self.x_packed, stream)
+            if down_packed and self.h_packed is None:
+                self.h_packed = torch.empty(
+                    (B.moe_packed_h_bytes(self.T * self.k, self.f, self.E),), dtype=torch.uint8,
+                    device=self.h.device)
+            # the data movement of the permute step, written once in the GEMM's own layout
+            B.moe_permute_rows_packed(x, self.row_src, self.k, self.expert_offsets,
+                                      self.T * self.k, self.x_packed, stream)
         if marks is not None:
             marks[2].record(stream)
-        if use_packed and self.pack_x:
+        if up_packed:
             B.moe_expert_up_swiglu_packed(self.x_packed, self.expert_offsets, packed["w_gate"],
-                                          packed["w_up"], self.T * self.k, self.h_packed, stream)
-        elif use_packed:
-            B.moe_expert_up_swiglu_gather_packed(x, self.row_src, self.k, self.expert_offsets,
-                                                 packed["w_gate"], packed["w_up"],
-                                                 self.T * self.k, self.h_packed, None, stream)
+                                          packed["w_up"], self.T * self.k,
+                                          self.h_packed if down_packed else self.h,
+                                          not down_packed, stream)
         elif self.fuse_gather:
             B.moe_expert_up_swiglu_gather(x, self.row_src, self.k, self.expert_offsets, w_gate,
                                           w_up, self.h, stream)
@@ -105,7 +115,7 @@ class MoEVerifyLayer:
             B.moe_expert_up_swiglu(self.x_perm, self.expert_offsets, w_gate, w_up, self.h, stream)
         if marks is not None:
             marks[3].record(stream)
-        if use_packed:
+        if down_packed:
             B.moe_expert_down_packed(self.h_packed, self.expert_offsets, packed["w_down"],
                                      self.y_perm, stream)
         else:

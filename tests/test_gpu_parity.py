@@ -330,10 +330,14 @@ def test_rmsnorm(dtype, T, d):
 
 
 # ------------------------------------------------------------------ whole layer
-def _run_layer(cfg, L):
+def _run_layer(cfg, L, packed=False):
+    """packed: hand the layer tile-packed copies of the expert weights as well (what the
+    benchmark does); the layer then runs the projections its plan assigns to them."""
     layer = sm.MoEVerifyLayer(L["x"].shape[0], cfg.d_model, cfg.d_ff, cfg.E, cfg.k,
                               cfg.torch_dtype, renorm=cfg.renorm)
-    out = layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"])
+    pk = sm.MoEVerifyLayer.pack_weights(L["w_gate"], L["w_up"], L["w_down"]) if packed else None
+    out = layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
+                        packed=pk)
     torch.cuda.synchronize()
     return layer, out
 
@@ -351,13 +355,16 @@ def _check_routing_and_permutation(cfg, L, layer):
     return counts
 
 
-@pytest.mark.parametrize("cfg_id", [1, 3])
-def test_layer_full_oracle(cfg_id):
-    """Configurations the oracle can evaluate in full in seconds."""
+@pytest.mark.parametrize("cfg_id,packed", [(1, False), (3, False), (3, True)])
+def test_layer_full_oracle(cfg_id, packed):
+    """Configurations the oracle can evaluate in full in seconds (cfg 3 on row-major operands
+    and, as the benchmark runs it, on tile-packed ones)."""
     cfg = synth.CONFIGS[cfg_id]
-    _say(f"layer cfg{cfg_id} full")
+    _say(f"layer cfg{cfg_id} full packed={packed}")
     L = synth.make_layer(cfg, "cuda", seed=cfg_id)
-    layer, out = _run_layer(cfg, L)
+    layer, out = _run_layer(cfg, L, packed)
+    if packed:
+        assert layer.x_packed is not None and layer.h_packed is not None
     counts = _check_routing_and_permutation(cfg, L, layer)
     want = orc.moe_layer_stepwise(f64(L["x"]), f64(L["w_router"]), LazyF64(L["w_gate"]),
                                   LazyF64(L["w_up"]), LazyF64(L["w_down"]), cfg.k,
@@ -366,9 +373,9 @@ def test_layer_full_oracle(cfg_id):
                 f"cfg{cfg_id} active={int((counts > 0).sum())}/{cfg.E} "
                 f"skew={orc.skewness(counts):.2f} hottest={int(counts.max())}")
     # run twice: deterministic, bit-identical
-    out2 = layer.forward(L["x"], L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"]).clone()
-    torch.cuda.synchronize()
-    assert torch.equal(out, out2)
+    out1 = out.clone()
+    _, out2 = _run_layer(cfg, L, packed)
+    assert torch.equal(out1, out2)
 
 
 def _seam_rows(offsets, bm_max=320, gran=16):
@@ -393,23 +400,26 @@ def _seam_rows(offsets, bm_max=320, gran=16):
     return sorted(rows)
 
 
-@pytest.mark.parametrize("cfg_id,n_random", [(2, 24), (4, 64), (6, 64)])
-def test_layer_sampled_tokens(cfg_id, n_random):
+@pytest.mark.parametrize("cfg_id,n_random,packed", [(2, 24, False), (4, 64, True), (6, 64, True),
+                                                    (6, 16, False)])
+def test_layer_sampled_tokens(cfg_id, n_random, packed):
     """Full-size layers (Mixtral shape; Llama-4-Scout shape with top-1 routing, Table I) in the
     launch configuration the benchmark times: routing and permutation checked in full; outputs
     on a token sample (tokens are independent, so the definition applies row by row).  The
     sample holds the tokens behind the seam rows of the expert kernels' tiling (mapped back
     through the oracle's row_src) plus seeded random tokens."""
     cfg = synth.CONFIGS[cfg_id]
-    _say(f"layer cfg{cfg_id} sampled")
+    _say(f"layer cfg{cfg_id} sampled packed={packed}")
     L = synth.make_layer(cfg, "cuda", seed=cfg_id)
-    layer, out = _run_layer(cfg, L)
+    layer, out = _run_layer(cfg, L, packed)
+    assert (layer.x_packed is not None) == packed
     _check_routing_and_permutation(cfg, L, layer)
     x64 = f64(L["x"])
     bias = None if L["bias"] is None else f64(L["bias"])
     eidx, _, _ = orc.route_topk(x64, f64(L["w_router"]), cfg.k, bias, cfg.renorm)
     _, eoff, ers, _ = orc.permute(eidx, cfg.E)
-    seam_tokens = {int(ers[r]) // cfg.k for r in _seam_rows(eoff)}
+    # tiles of at most 320 rows (from 192 rows per expert on average) or 192 rows (below)
+    seam_tokens = {int(ers[r]) // cfg.k for bm in (320, 192) for r in _seam_rows(eoff, bm)}
     rng = np.random.default_rng(cfg_id)
     sample = np.array(sorted(seam_tokens | set(rng.choice(cfg.T, size=n_random, replace=False).tolist())))
     print(f"   cfg{cfg_id}: {len(seam_tokens)} seam tokens, {len(sample)} tokens in all", flush=True)
@@ -659,6 +669,11 @@ def test_packed_expert_gemms(d, f, rows):
     xws3 = torch.full_like(xws, 0xbb)
     sm.moe_permute_rows_packed(dev(xp), None, 1, doff, n, xws3)
     sm.moe_expert_up_swiglu_packed(xws3, doff, pk["w_gate"], pk["w_up"], n, hp3)
+    # ... and with h written row-major for the row-major down projection
+    h_rm = torch.full((n, f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    y4 = torch.full_like(y, float("nan"))
+    sm.moe_expert_up_swiglu_packed(xws3, doff, pk["w_gate"], pk["w_up"], n, h_rm, h_row_major=True)
+    sm.moe_expert_down(h_rm, doff, dev(wd), y4)
     torch.cuda.synchronize()
     assert torch.equal(y.view(torch.int16), y3.view(torch.int16))
     used = (sum((r + 15) // 16 for r in rows)) * 16 * f * 2          # blocks the batch really uses
@@ -674,8 +689,16 @@ def test_packed_expert_gemms(d, f, rows):
         b += (r + 15) // 16
     assert (xws3[:usedx].cpu().view(torch.int16).numpy() ==
             _tile_packed(xpad[None]).reshape(-1)).all()
+    # row-major h = the packed h, un-tiled (same kernel arithmetic, only the store differs)
+    hpad = torch.zeros(used // (2 * f), f, dtype=torch.bfloat16)
+    b = 0
+    for e, r in enumerate(rows):
+        hpad[16 * b:16 * b + r] = h_rm[off[e]:off[e + 1]].cpu()
+        b += (r + 15) // 16
+    assert (hp3[:used].cpu().view(torch.int16).numpy() == _tile_packed(hpad[None]).reshape(-1)).all()
     ey = orc.grouped_swiglu(f64(xp), off, LazyF64(wg), LazyF64(wu), LazyF64(wd))
     check_float(f64(y), ey, torch.bfloat16, f"packed rows={rows}")
+    check_float(f64(y4), ey, torch.bfloat16, f"packed up, row-major down rows={rows}")
     if n >= 192 * E:
         y2 = _gpu_grouped(xp, torch.from_numpy(off), wg, wu, wd)
         assert torch.equal(y.cpu().view(torch.int16), y2.view(torch.int16))
@@ -695,3 +718,28 @@ def test_layer_cfg4_packed_path():
     torch.cuda.synchronize()
     assert layer.h_packed is not None
     assert torch.equal(ref.view(torch.int16), out2.view(torch.int16))
+
+
+@pytest.mark.parametrize("name,cfg,plan", [
+    ("short-k-all-packed", synth.MoEConfig("p1", "bf16", 256, 384, 8, 2, 10, 3, 1 / 16, 0.05, 1.0),
+     (True, True)),
+    ("up-packed-down-row-major", synth.MoEConfig("p2", "bf16", 256, 4096, 4, 2, 25, 3, 1 / 16, 0.05, 1.0),
+     (True, False)),
+    ("long-k-96-rows-all-packed", synth.MoEConfig("p3", "bf16", 256, 4096, 2, 2, 25, 3, 1 / 16, 0.05, 1.0),
+     (True, True)),
+    ("long-k-few-rows-row-major", synth.MoEConfig("p4", "bf16", 4096, 256, 4, 2, 10, 3, 1 / 64, 0.05, 1.0),
+     (False, False)),
+])
+def test_layer_packed_plans(name, cfg, plan):
+    """Every combination the layer's plan can pick (gate/up and down each on tile-packed or on
+    row-major operands, h in the layout the down projection reads) against the full oracle."""
+    _say(f"layer packed plan {name}")
+    assert sm.MoEVerifyLayer.packed_plan(cfg.T * cfg.k, cfg.E, cfg.d_model, cfg.d_ff) == plan
+    L = synth.make_layer(cfg, "cuda", seed=31)
+    layer, out = _run_layer(cfg, L, packed=True)
+    assert (layer.x_packed is not None) == plan[0]
+    assert (layer.h_packed is not None) == plan[1]
+    _check_routing_and_permutation(cfg, L, layer)
+    want = orc.moe_layer_brute_force(f64(L["x"]), f64(L["w_router"]), LazyF64(L["w_gate"]),
+                                     LazyF64(L["w_up"]), LazyF64(L["w_down"]), cfg.k)
+    check_float(f64(out), want, cfg.torch_dtype, name)

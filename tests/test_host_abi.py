@@ -85,11 +85,12 @@ def test_packed_entry_points_validation(lib):
     assert rows(P, N, 0, 1, P, 64, 64, 2, 1, P, 16, N) == 4              # x_packed too small
     assert rows(P, N, 0, 1, N, 64, 64, 2, 1, P, big, N) == 1
     assert rows(N, N, 0, 1, N, 0, 64, 2, 1, N, 0, N) == 0                # nothing to do
-    assert upp(P, big, P, P, P, 64, 64, 64, 2, 0, P, big, N) == 3
-    assert upp(P, 16, P, P, P, 64, 64, 64, 2, 1, P, big, N) == 4         # x_packed too small
-    assert upp(P, big, P, P, P, 64, 64, 64, 2, 1, P, 16, N) == 4         # h_packed too small
-    assert upp(N, big, P, P, P, 64, 64, 64, 2, 1, P, big, N) == 1
-    assert upp(P, big, P, P, P, 64, 64, 100, 2, 1, P, big, N) == 2
+    assert upp(P, big, P, P, P, 64, 64, 64, 2, 0, P, big, 0, N) == 3
+    assert upp(P, 16, P, P, P, 64, 64, 64, 2, 1, P, big, 0, N) == 4      # x_packed too small
+    assert upp(P, big, P, P, P, 64, 64, 64, 2, 1, P, 16, 0, N) == 4      # h_packed too small
+    assert upp(P, big, P, P, P, 64, 64, 64, 2, 1, P, 64 * 64 * 2 - 1, 1, N) == 4   # row-major h too small
+    assert upp(N, big, P, P, P, 64, 64, 64, 2, 1, P, big, 0, N) == 1
+    assert upp(P, big, P, P, P, 64, 64, 100, 2, 1, P, big, 0, N) == 2
 
 
 def test_route_validation(lib):
