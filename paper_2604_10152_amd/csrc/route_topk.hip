@@ -268,15 +268,34 @@ template <typename T, int V>
 void launch_typed(const void* x, const void* wr, const float* bias, int Tn, int d, int E, int k,
                   int renorm, int32_t* idx, float* w, const int32_t* remap, hipStream_t s) {
     const bool vec = (d % V == 0) && ((((uintptr_t)x | (uintptr_t)wr) & 15u) == 0);
-    // One token per workgroup while two workgroups per CU cover the batch (a single pass over
-    // the experts, nothing converted twice); beyond that 4 tokens share every widened router
-    // weight.
-    const bool many = Tn > 512;
     const T* xt = (const T*)x;
     const T* wt = (const T*)wr;
-    if (vec && many) launch_by_experts<T, true, 4>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
-    else if (vec) launch_by_experts<T, true, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
-    else launch_by_experts<T, false, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    if (!vec) {
+        launch_by_experts<T, false, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+        return;
+    }
+    // Tokens per workgroup.  The kernel is bound by the widening conversions to fp64 (about 8x
+    // the cost of an fp64 FMA per instruction; its time does not depend on d_model below one
+    // chunk per lane and does not depend on k).  Per SIMD of the busiest CU they number
+    //   workgroups per CU x 4 waves x passes x 8 x (TOK + EC)
+    // (every group of 4 waves widens its TOK token chunks and its EC router chunks per pass;
+    // passes x EC covers a quarter of the experts).  More tokens per workgroup share the
+    // widened router weights but leave CUs idle while the batch is small: take the minimum.
+    int best_tok = 1;
+    long long best = -1;
+    for (int tok = 1; tok <= 4; tok *= 2) {
+        const int ec_max = 16 / tok;
+        int ec = 1;
+        while (ec < ec_max && ec * kRouteGroups < E) ec *= 2;
+        const long long passes = (E + kRouteGroups * ec - 1) / (kRouteGroups * ec);
+        const long long wgs = (Tn + tok - 1) / tok;
+        const long long per_cu = (wgs + 255) / 256;
+        const long long load = per_cu * passes * (tok + ec);
+        if (best < 0 || load < best) { best = load; best_tok = tok; }
+    }
+    if (best_tok == 4) launch_by_experts<T, true, 4>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else if (best_tok == 2) launch_by_experts<T, true, 2>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
+    else launch_by_experts<T, true, 1>(xt, wt, bias, Tn, d, E, k, renorm, idx, w, remap, s);
 }
 
 }  // namespace
