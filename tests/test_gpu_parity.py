@@ -639,6 +639,9 @@ def test_pack_weights_layout(E, R, K):
     (512, 1408, [700, 650]),
     (256, 384, [3, 0, 70, 1, 129, 64, 0, 0]),        # few rows: still correct on the packed path
     (64, 64, [1]),
+    # more experts than lanes: the block numbering carries over the 64-expert sweeps of the scans
+    (128, 128, [(7 * e) % 23 if e % 3 else 0 for e in range(130)]),
+    (128, 64, [0] * 70 + [200, 17] + [0] * 60 + [33]),
 ])
 def test_packed_expert_gemms(d, f, rows):
     """moe_expert_up_swiglu_gather_packed + moe_expert_down_packed against the oracle, and - where
