@@ -642,6 +642,10 @@ def test_pack_weights_layout(E, R, K):
     # more experts than lanes: the block numbering carries over the 64-expert sweeps of the scans
     (128, 128, [(7 * e) % 23 if e % 3 else 0 for e in range(130)]),
     (128, 64, [0] * 70 + [200, 17] + [0] * 60 + [33]),
+    # few rows per expert, longer contractions: ragged and empty experts on the 192-row tiles
+    (256, 512, [3, 0, 70, 1, 129, 64, 0, 0]),
+    (128, 256, [5, 17, 64, 1, 0, 33, 65, 16]),
+    (512, 1024, [40, 1]),
 ])
 def test_packed_expert_gemms(d, f, rows):
     """moe_expert_up_swiglu_gather_packed + moe_expert_down_packed against the oracle, and - where
