@@ -637,7 +637,8 @@ def main():
             run.layer.forward(run.x, L["w_router"], L["w_gate"], L["w_up"], L["w_down"], L["bias"],
                               stream=st, packed=packed),
             sm.spec_accept(run.draft_d, run.target_d, run.alen, run.toks, st)))
-        for _ in range(max(1, args.warmup // 2)):
+        run.settle()
+        for _ in range(args.warmup):
             graphed.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
