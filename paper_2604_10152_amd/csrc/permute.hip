@@ -2,7 +2,7 @@
 // (SpecMoE Fig. 2: tokens that activate the same expert are served together; Sec. 3.2: the
 // per-expert activation counts of the verification pass are the differences of expert_offsets.)
 //
-// Index phase: ONE workgroup of 8 wavefronts.  Wave w owns the w-th contiguous slice of the
+// Index phase: ONE workgroup of 16 wavefronts (8 beyond 64 experts).  Wave w owns the w-th contiguous slice of the
 // flat pair array.  (A) per-wave, per-expert counts in LDS (integer atomics: order-free);
 // (B) totals -> exclusive prefix sum over experts -> each wave's first destination row per
 // expert; (C) every wave walks its slice in order, 64 pairs at a time, ranks equal experts
@@ -14,17 +14,20 @@
 namespace specmoe {
 namespace {
 
-constexpr int kPermWaves = 8;
-constexpr int kPermThreads = kPermWaves * kWave;
+constexpr int kPermWavesSmallE = 16;   // E <= 64: shorter slices per wave (the walk is serial)
+constexpr int kPermWavesLargeE = 8;    // (waves + 1) * E counters have to fit the LDS default
 constexpr int kBatch = 8;          // index rows fetched ahead per wavefront
 
 // SMALL_E (E <= 64): in phase (C) lane e keeps expert e's cursor in a register and the loop
 // over the distinct experts of a 64-pair row uses readlane instead of an LDS read-modify-write
 // chain (the chain dominated the kernel: 19 -> ~9 us at 4096 pairs).
 template <bool SMALL_E>
-__global__ __launch_bounds__(kPermThreads) void permute_index_kernel(
+__global__ __launch_bounds__((SMALL_E ? kPermWavesSmallE : kPermWavesLargeE) * kWave)
+void permute_index_kernel(
     const int32_t* __restrict__ idx, int P, int E, int32_t* __restrict__ offsets,
     int32_t* __restrict__ row_src, int32_t* __restrict__ row_of) {
+    constexpr int kPermWaves = SMALL_E ? kPermWavesSmallE : kPermWavesLargeE;
+    constexpr int kPermThreads = kPermWaves * kWave;
     extern __shared__ int lds[];             // wave_cnt[kPermWaves][E], excl[E]
     int* wave_cnt = lds;
     int* excl = lds + kPermWaves * E;
@@ -40,8 +43,10 @@ __global__ __launch_bounds__(kPermThreads) void permute_index_kernel(
     int* mine = wave_cnt + wave * E;
 
     // (A) counts.  Indices are fetched kBatch wavefront-rows at a time so the loads overlap.
+    // A slice of at most one such batch stays in registers for phase (C).
+    const bool one_batch = per_wave <= kWave * kBatch;
+    int ev[kBatch];
     for (int base = lo; base < hi; base += kWave * kBatch) {
-        int ev[kBatch];
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) {
             const int p = base + b * kWave + lane;
@@ -91,11 +96,11 @@ __global__ __launch_bounds__(kPermThreads) void permute_index_kernel(
     const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
     int cursor = (SMALL_E && lane < E) ? mine[lane] : 0;                // lane e: cursor of expert e
     for (int base0 = lo; base0 < hi; base0 += kWave * kBatch) {         // (C)
-        int ev[kBatch];
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) {
             const int p = base0 + b * kWave + lane;
-            ev[b] = (p < hi) ? min(max(idx[p], 0), E - 1) : -1;
+            const int raw = one_batch ? ev[b] : ((p < hi) ? idx[p] : -1);
+            ev[b] = (p < hi) ? min(max(raw, 0), E - 1) : -1;
         }
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) {
@@ -148,13 +153,14 @@ hipError_t launch_permute(const void* x, const int32_t* idx, int T, int d, int E
                           int dtype, void* x_perm, int32_t* offsets, int32_t* row_src,
                           int32_t* row_of, hipStream_t s) {
     const int P = T * k;
-    size_t lds = (size_t)(kPermWaves + 1) * E * sizeof(int);
     if (E <= kWave)
-        hipLaunchKernelGGL(permute_index_kernel<true>, dim3(1), dim3(kPermThreads), lds, s, idx, P,
-                           E, offsets, row_src, row_of);
+        hipLaunchKernelGGL(permute_index_kernel<true>, dim3(1), dim3(kPermWavesSmallE * kWave),
+                           (size_t)(kPermWavesSmallE + 1) * E * sizeof(int), s, idx, P, E, offsets,
+                           row_src, row_of);
     else
-        hipLaunchKernelGGL(permute_index_kernel<false>, dim3(1), dim3(kPermThreads), lds, s, idx,
-                           P, E, offsets, row_src, row_of);
+        hipLaunchKernelGGL(permute_index_kernel<false>, dim3(1), dim3(kPermWavesLargeE * kWave),
+                           (size_t)(kPermWavesLargeE + 1) * E * sizeof(int), s, idx, P, E, offsets,
+                           row_src, row_of);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || x_perm == nullptr || P == 0) return err;
     const size_t row_bytes = (size_t)d * (dtype == 0 ? 4 : 2);
