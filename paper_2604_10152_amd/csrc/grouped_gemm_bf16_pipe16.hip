@@ -1,4 +1,5 @@
-// Large-batch expert GEMMs, v_mfma_f32_16x16x32_bf16 flavour of the pipelined kernel.
+// Large- and mid-batch expert GEMMs (tiles of up to 320 or 192 rows), v_mfma_f32_16x16x32_bf16
+// flavour of the pipelined kernel.
 // (SpecMoE Sec. 2.1 / 2.2: the rows routed to an expert meet its FFN-sized weights; at
 // verification time each expert sees hundreds of rows, so the contraction is MFMA-bound.)
 //
@@ -335,8 +336,9 @@ hipError_t launch_expert_down_bf16_large16(const bf16_t* h, const int32_t* offse
                                                                 d, f, y, s);
 }
 
-// Tile-packed variants (any batch size; meant for the large-batch regime): weights packed by
-// moe_pack_weights, h tile-packed between the two projections.
+// Tile-packed variants: weights packed by moe_pack_weights, h tile-packed between the two
+// projections.  This one gathers the token rows itself from the row-major token matrix (per-lane
+// row addresses, 64-byte requests on the activation side) and always uses 320-row tiles.
 hipError_t launch_expert_up_bf16_packed(const bf16_t* x, const int32_t* offsets,
                                         const bf16_t* wg_packed, const bf16_t* wu_packed,
                                         int n_rows, int d, int f, int E, bf16_t* h_packed,

@@ -273,8 +273,8 @@ hipError_t launch_one(const bf16_t* A, const int32_t* offsets, const bf16_t* W0,
 }  // namespace
 
 // Rows per expert (average) from which a kernel family applies: >= 192 large (MFMA-bound,
-// up to 320-row tiles), >= 48 with a long contraction mid (128-row tiles), below that small
-// (64-row tiles).
+// up to 320-row tiles), >= 48 with a long contraction mid (gate/up: up to 192-row tiles of the
+// same kernel; down: 128-row tiles of the 32x32x16 pipeline), below that small (64-row tiles).
 constexpr int g_large_rows = 192, g_mid_rows = 48;
 static inline bool large_batch(int n_rows, int E) {
     return (long long)n_rows >= (long long)g_large_rows * E;
