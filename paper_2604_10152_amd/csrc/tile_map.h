@@ -19,6 +19,7 @@ struct TileLoc {
     int nt;          // n-tile index
     int blk0;        // 16-row blocks in front of the tile when every expert's rows are padded to
                      // a whole number of blocks (row numbering of the tile-packed matrices)
+    int mt;          // m-tiles of the tile's expert (1: its weight tiles are read by one workgroup)
 };
 
 // Even split: an expert with M rows gets ceil(M / BM_MAX) m-tiles of equal height (rounded up
@@ -75,7 +76,7 @@ __device__ __forceinline__ bool locate_tile_impl(const int32_t* __restrict__ off
     if (slot >= per_xcd || L >= G) return false;
     int base_mt = 0;                              // m-tiles of the experts before this sweep
     int base_blk = 0;                             // 16-row blocks of the experts before this sweep
-    int expert = -1, row0 = 0, rows = 0, nt = 0, blk0 = 0;
+    int expert = -1, row0 = 0, rows = 0, nt = 0, blk0 = 0, mts = 0;
     for (int e0 = 0; e0 < E && expert < 0; e0 += kWave) {
         const int e = e0 + lane;
         const int lo = e < E ? offsets[e] : 0, hi = e < E ? offsets[e + 1] : 0;
@@ -99,6 +100,7 @@ __device__ __forceinline__ bool locate_tile_impl(const int32_t* __restrict__ off
             nt = (int)(rem / mt);
             const int mi = (int)(rem - (long long)nt * mt);
             expert = e0 + src;
+            mts = mt;
             row0 = lo_s + mi * rpt;
             rows = min(rpt, hi_s - row0);
             blk0 = base_blk + __shfl(incl_blk, src, kWave) - __shfl(nblk, src, kWave) +
@@ -113,6 +115,7 @@ __device__ __forceinline__ bool locate_tile_impl(const int32_t* __restrict__ off
     t.tile_rows = __builtin_amdgcn_readfirstlane(rows);
     t.nt = __builtin_amdgcn_readfirstlane(nt);
     t.blk0 = __builtin_amdgcn_readfirstlane(blk0);
+    t.mt = __builtin_amdgcn_readfirstlane(mts);
     return t.expert >= 0;
 }
 
