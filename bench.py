@@ -489,6 +489,15 @@ def peaks_bench(args):
                               "contiguous_bytes_per_row_piece": seg, "workgroups": blocks, "ms": ms,
                               "bytes": nbytes, "measured_gbs": nbytes / ms / 1e6,
                               "published_hbm_gbs": PEAK_HBM_GBS}), flush=True)
+    # the same stream out of HBM with the non-temporal hint (what the expert GEMMs use for
+    # weight tiles that no other workgroup reads)
+    region = 4 << 30
+    ms, nbytes = timed(lambda: peaks.l2_lds_nt(buf, region, region // (256 << 10), 1, st))
+    print(json.dumps({"peak": "global_load_lds_dwordx4_stream",
+                      "source": "HBM (4 GiB read once), non-temporal hint",
+                      "contiguous_bytes_per_row_piece": 1024, "workgroups": region // (256 << 10),
+                      "ms": ms, "bytes": nbytes, "measured_gbs": nbytes / ms / 1e6,
+                      "published_hbm_gbs": PEAK_HBM_GBS}), flush=True)
 
 
 def traffic_run(args):

@@ -110,7 +110,8 @@ __global__ __launch_bounds__(256) void hbm_read_loop(const U128* __restrict__ p,
 // SEG = contiguous bytes per row piece: 1024 (a wave-load is 1 KB of consecutive memory), 128
 // (8 rows x one whole line, rows 8 KB apart: what a BK = 64 stage asks for) or 64 (16 rows x half
 // a line: a BK = 32 stage).
-template <int SEG>
+// NT: the loads carry the non-temporal hint (data read once).
+template <int SEG, bool NT = false>
 __global__ __launch_bounds__(512) void l2_lds_loop(const unsigned char* __restrict__ buf,
                                                    size_t region_bytes, int iters) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
@@ -138,7 +139,8 @@ __global__ __launch_bounds__(512) void l2_lds_loop(const unsigned char* __restri
                     constexpr uint32_t RB = 32 / RPL;
                     off = (q % RB) * RPL * kPitch + (q / RB) * SEG;
                 }
-                dma16(base, off + lane_off, lds_base + ((u * 8 + wave) * 1024u));
+                if (NT) dma16_nt(base, off + lane_off, lds_base + ((u * 8 + wave) * 1024u));
+                else dma16(base, off + lane_off, lds_base + ((u * 8 + wave) * 1024u));
             }
             wait_vmcnt<8>();
         }
@@ -238,6 +240,17 @@ int specmoe_peak_l2_lds(const void* buf, size_t region_bytes, int blocks, int it
     else if (seg == 128) hipLaunchKernelGGL(l2_lds_loop<128>, dim3(blocks), dim3(512), 32768, s, b, region_bytes, iters);
     else if (seg == 64) hipLaunchKernelGGL(l2_lds_loop<64>, dim3(blocks), dim3(512), 32768, s, b, region_bytes, iters);
     else return 1;
+    return hipGetLastError() == hipSuccess ? 0 : 5;
+}
+
+// The 1024-byte-piece stream of specmoe_peak_l2_lds with the non-temporal hint on the loads.
+int specmoe_peak_l2_lds_nt(const void* buf, size_t region_bytes, int blocks, int iters,
+                           void* stream) {
+    if (!buf || blocks < 1 || iters < 1 || region_bytes < (256u << 10) ||
+        region_bytes % (256u << 10) != 0)
+        return 1;
+    hipLaunchKernelGGL((l2_lds_loop<1024, true>), dim3(blocks), dim3(512), 32768,
+                       (hipStream_t)stream, (const unsigned char*)buf, region_bytes, iters);
     return hipGetLastError() == hipSuccess ? 0 : 5;
 }
 

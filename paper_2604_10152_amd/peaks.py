@@ -21,6 +21,7 @@ def load():
         lib.specmoe_peak_mfma.argtypes = [i, i, i, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
         lib.specmoe_peak_hbm_read.argtypes = [vp, sz, i, vp, vp]
         lib.specmoe_peak_l2_lds.argtypes = [vp, sz, i, i, i, vp]
+        lib.specmoe_peak_l2_lds_nt.argtypes = [vp, sz, i, i, vp]
         lib.specmoe_peak_lds_read.argtypes = [i, i, vp, vp, vp]
         _LIB = lib
     return _LIB
@@ -47,6 +48,12 @@ def hbm_read(buf, blocks, sink, stream):
 def l2_lds(buf, region_bytes, blocks, iters, seg, stream):
     _check(load().specmoe_peak_l2_lds(buf.data_ptr(), region_bytes, blocks, iters, seg,
                                       stream.cuda_stream), "specmoe_peak_l2_lds")
+    return blocks * iters * (256 << 10)
+
+
+def l2_lds_nt(buf, region_bytes, blocks, iters, stream):
+    _check(load().specmoe_peak_l2_lds_nt(buf.data_ptr(), region_bytes, blocks, iters,
+                                         stream.cuda_stream), "specmoe_peak_l2_lds_nt")
     return blocks * iters * (256 << 10)
 
 
