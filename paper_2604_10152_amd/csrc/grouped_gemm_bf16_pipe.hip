@@ -264,7 +264,9 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe_kernel(
     // once - a pure stream out of HBM, which the non-temporal hint speeds up (6.3 vs 5.7 TB/s on a
     // plain LDS-DMA stream).  With several m-tiles the workgroups that share a weight tile meet
     // in the L2, and the hint would cost those hits.
-    const bool w_once = t.mt == 1 && (!C::SWIGLU || tile_rows <= 64);
+    // (whole 128-byte lines per row and stage only: half-line loads rely on the L2 keeping the
+    // other half for the next stage)
+    const bool w_once = C::ROW_BYTES >= 128 && t.mt == 1 && (!C::SWIGLU || tile_rows <= 64);
     auto run_sel = [&](auto ta_tag) __attribute__((always_inline)) {
         if (w_once) run(ta_tag, std::true_type{});
         else run(ta_tag, std::false_type{});

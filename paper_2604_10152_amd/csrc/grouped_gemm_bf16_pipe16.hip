@@ -290,7 +290,10 @@ __global__ __launch_bounds__(C::THREADS) void grouped_gemm_bf16_pipe16_kernel(
     // once - a pure stream out of HBM, which the non-temporal hint speeds up (6.3 vs 5.7 TB/s on a
     // plain LDS-DMA stream).  With several m-tiles the workgroups that share a weight tile meet
     // in the L2, and the hint would cost those hits.
-    const bool w_once = t.mt == 1 && (!C::SWIGLU || tile_rows <= 64);
+    // Only with tile-packed weights: a wave-load then covers whole 128-byte lines.  Row-major, a
+    // BK = 32 stage takes half of every line and the next stage the other half; without
+    // allocation in the L2 every line would come out of HBM twice (measured: 363 -> 469 us).
+    const bool w_once = PB && t.mt == 1 && (!C::SWIGLU || tile_rows <= 64);
     auto run_sel = [&](auto ta_tag) __attribute__((always_inline)) {
         if (w_once) run_pp(ta_tag, std::true_type{});
         else run_pp(ta_tag, std::false_type{});
